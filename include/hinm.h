@@ -1,0 +1,152 @@
+/*
+ * hinm.h -- C ABI of the HiNM sparse-GEMM library for AMD MI355X (gfx950).
+ *
+ * Hierarchical N:M (HiNM) sparsity, arXiv 2407.20496:
+ *   Section 1 (Figure 1): a dense weight matrix W (M output channels x K input
+ *   channels) is pruned in two levels.  Inside every tile of V consecutive
+ *   output channels whole V x 1 column vectors are removed until Kv of the K
+ *   columns survive; the surviving columns are listed in the tile's *vector
+ *   index*.  Then every row of the tile is pruned 2:4 over consecutive groups
+ *   of four surviving columns; the two kept positions of each group form the
+ *   *NM index*, and the kept values are stored densely.
+ *   Section 3.2 / Section 5.3: at run time the product reads only the input
+ *   rows named by the vector index, and channel re-ordering is absorbed into
+ *   that indexing, so each layer may use its own input- and output-channel
+ *   order with no separate permute pass:
+ *         Y = P_out ( W_HiNM ( P_in X ) ).
+ *
+ * Conventions shared by all entry points
+ *   - Row-major matrices.  W is M x K, X is K x N (leading dimension ldx
+ *     elements), Y is M x N (leading dimension ldy elements).
+ *   - T = M / V tiles.  Kv kept columns per tile; Kv/2 stored values per row.
+ *   - Canonical packed form (what parity is judged on):
+ *       vals    16-bit values  [M][Kv/2]  for group g of row r: the two kept
+ *                                         values in ascending position order
+ *                                         at [r][2g], [r][2g+1] (bit copies of W)
+ *       nm_idx  uint8          [M][Kv/8]  nibble of group g = p0 | (p1 << 2),
+ *                                         p0 < p1 the kept positions (0..3);
+ *                                         group g sits in byte g/2, bits
+ *                                         4*(g&1) .. 4*(g&1)+3
+ *       vec_idx int32          [T][Kv]    surviving columns of tile t, ascending;
+ *                                         group g covers entries 4g .. 4g+3
+ *   - Channel orders: pi_in is int32[K], row k of (P_in X) is row pi_in[k] of X
+ *     (gather); pi_out is int32[M], row r of W_HiNM(P_in X) is written to row
+ *     pi_out[r] of Y (scatter).  NULL means identity.  They are not checked
+ *     for being bijections; entries must lie in [0,K) resp. [0,M).
+ *   - Selection rules of hinm_pack: vector saliency = sum of squares of the V
+ *     entries, accumulated in IEEE binary64 in ascending row order; the Kv
+ *     largest survive, equal scores -> lower column.  2:4 saliency = |w|
+ *     (compared on the 15 magnitude bits), equal -> lower position; always
+ *     exactly two survivors per group, explicit zeros included.
+ *   - Pointers: `hinm_shape` / `hinm_layer` arguments are HOST memory, read
+ *     during the call only.  Every other pointer is DEVICE memory owned by the
+ *     caller; the library allocates nothing, keeps no reference after the
+ *     work is enqueued, and the caller keeps buffers alive until `stream`
+ *     (a hipStream_t, NULL = the default stream) has passed that work.
+ *     All work is asynchronous on `stream`; no entry point synchronises.
+ *   - Errors: a status code is returned; argument errors are detected on the
+ *     host before anything is launched (so they can be tested without a GPU).
+ *     HINM_ERR_DEVICE reports a failed launch.  W must be finite.
+ *   - Alignment: vals, X and Y base pointers 16-byte aligned; ldx, ldy
+ *     multiples of 8 elements unless N == 1 (then any ld >= 1).
+ */
+#ifndef HINM_H
+#define HINM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HINM_OK = 0,
+  HINM_ERR_NULL = 1,        /* a required pointer is NULL */
+  HINM_ERR_SHAPE = 2,       /* M % V != 0, Kv % 8 != 0, Kv > K, non-positive size, bad ld / alignment */
+  HINM_ERR_DTYPE = 3,       /* dtype is neither HINM_F16 nor HINM_BF16 */
+  HINM_ERR_WORKSPACE = 4,   /* workspace / scratch missing or too small */
+  HINM_ERR_UNSUPPORTED = 5, /* valid request this build has no kernel for (e.g. forced kernel vs. shape) */
+  HINM_ERR_DEVICE = 6       /* HIP reported an error at launch */
+} hinm_status;
+
+typedef enum { HINM_F16 = 0, HINM_BF16 = 1 } hinm_dtype;
+
+/* flags of hinm_spmm / hinm_layer (bit-or) */
+enum {
+  HINM_EPI_RELU = 1u,         /* y = max(y, 0) before rounding (used between chained layers) */
+  HINM_OUT_F32 = 2u,          /* Y is float32 [M][N]: the un-rounded accumulators (verification mode) */
+  /* kernel choice; default (none set) picks by shape */
+  HINM_KERNEL_REFERENCE = 0x100u, /* one thread per output element, plain FMA; any V */
+  HINM_KERNEL_SMFMAC = 0x200u,    /* sparse-MFMA tile kernel; needs V in {16,32,64,96,128} */
+  HINM_KERNEL_GEMV = 0x400u       /* wavefront-per-row kernel for very small N (N <= 8) */
+};
+
+typedef struct {
+  int32_t M;     /* output channels (rows of W) */
+  int32_t K;     /* input channels (columns of W) */
+  int32_t V;     /* vector height = rows per tile; M % V == 0 */
+  int32_t Kv;    /* surviving columns per tile; 0 < Kv <= K, Kv % 8 == 0 */
+  int32_t dtype; /* hinm_dtype of W, vals, X and (unless HINM_OUT_F32) Y */
+} hinm_shape;
+
+/* Size in bytes of the three packed arrays and of hinm_pack's workspace
+ * (one binary64 score per tile and column).  Any output pointer may be NULL. */
+hinm_status hinm_pack_sizes(const hinm_shape* shape, size_t* vals_bytes, size_t* nm_bytes,
+                            size_t* vec_bytes, size_t* workspace_bytes);
+
+/* Section 1 / Section 3.1: dense W [M][K] -> canonical packed arrays, on the
+ * GPU, following the selection rules above.  `workspace` needs
+ * workspace_bytes from hinm_pack_sizes and 8-byte alignment. */
+hinm_status hinm_pack(const hinm_shape* shape, const void* W,
+                      void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Inverse of hinm_pack: W_out [M][K] = W_HiNM (zeros where pruned).
+ * W_out is fully overwritten. */
+hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx,
+                        const int32_t* vec_idx, void* W_out, void* stream);
+
+/* Section 3.2 / Section 5.3: Y = P_out ( W_HiNM ( P_in X ) ), fp32 accumulation,
+ * output rounded to nearest-even in the storage type (or written as float32
+ * with HINM_OUT_F32).  Input rows are fetched through vec_idx composed with
+ * pi_in; output rows are stored through pi_out.  N >= 1.  X and Y must not
+ * overlap.  workspace may be NULL (no kernel of this build needs one). */
+hinm_status hinm_spmm(const hinm_shape* shape, int32_t N,
+                      const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
+                      const int32_t* pi_in, const int32_t* pi_out,
+                      const void* X, int64_t ldx, void* Y, int64_t ldy,
+                      uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
+
+typedef struct {
+  hinm_shape shape;
+  const void* vals;
+  const uint8_t* nm_idx;
+  const int32_t* vec_idx;
+  const int32_t* pi_in;   /* NULL = identity */
+  const int32_t* pi_out;  /* NULL = identity */
+  uint32_t flags;         /* HINM_EPI_RELU and kernel choice; HINM_OUT_F32 only on the last layer */
+} hinm_layer;
+
+/* Bytes of `scratch` hinm_chain needs for L layers at N columns (the
+ * intermediates between layers, in the storage type). */
+hinm_status hinm_chain_sizes(int32_t L, const hinm_layer* layers, int32_t N, size_t* scratch_bytes);
+
+/* Section 3.2 ("maintaining layer consistency"): L consecutive layers, layer
+ * l+1's K equal to layer l's M and the same dtype.  Every layer writes its
+ * output rows in its own pi_out order and the next layer reads them through
+ * its own pi_in; no permute kernel runs in between.  Intermediates are rounded
+ * to the storage type.  `scratch` is 256-byte aligned device memory. */
+hinm_status hinm_chain(int32_t L, const hinm_layer* layers, int32_t N,
+                       const void* X, int64_t ldx, void* Y, int64_t ldy,
+                       void* scratch, size_t scratch_bytes, void* stream);
+
+const char* hinm_status_str(hinm_status s);
+
+/* Library version, 1000*major + minor. */
+int32_t hinm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HINM_H */

@@ -1,0 +1,18 @@
+"""HiNM sparse GEMM with fused channel permutation for AMD MI355X (gfx950).
+
+Thin binding over the C ABI in ``include/hinm.h`` (``libhinm.so``): argument
+marshalling only -- every step of the path runs in the HIP kernels.  PyTorch is
+used for device memory and streams.  There is no CPU fallback: if the shared
+library is missing, every call raises.
+
+16-bit tensors may be passed as ``torch.float16`` / ``torch.bfloat16`` or as
+``torch.int16``/``torch.uint16`` bit patterns together with ``dtype="f16"|"bf16"``.
+"""
+from __future__ import annotations
+
+from .binding import (  # noqa: F401
+    F16, BF16, EPI_RELU, OUT_F32, KERNEL_REFERENCE, KERNEL_SMFMAC, KERNEL_GEMV,
+    HinmError, Layer, library_path, load_library, exported_symbols,
+    hinm_pack_sizes, hinm_pack, hinm_unpack, hinm_spmm, hinm_chain_sizes, hinm_chain,
+    hinm_status_str, hinm_version,
+)

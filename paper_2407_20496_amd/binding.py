@@ -1,0 +1,188 @@
+"""ctypes binding of libhinm.so; names mirror include/hinm.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+F16, BF16 = 0, 1
+EPI_RELU, OUT_F32 = 1, 2
+KERNEL_REFERENCE, KERNEL_SMFMAC, KERNEL_GEMV = 0x100, 0x200, 0x400
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhinm.so")
+_lib = None
+
+
+class HinmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({hinm_status_str(status)})")
+
+
+class _Shape(C.Structure):
+    _fields_ = [("M", C.c_int32), ("K", C.c_int32), ("V", C.c_int32), ("Kv", C.c_int32), ("dtype", C.c_int32)]
+
+
+class _Layer(C.Structure):
+    _fields_ = [("shape", _Shape), ("vals", C.c_void_p), ("nm_idx", C.c_void_p), ("vec_idx", C.c_void_p),
+                ("pi_in", C.c_void_p), ("pi_out", C.c_void_p), ("flags", C.c_uint32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def exported_symbols() -> Tuple[str, ...]:
+    """Entry points include/hinm.h declares."""
+    return ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain",
+            "hinm_status_str", "hinm_version")
+
+
+def load_library():
+    """Load libhinm.so (built in-tree by ``python -m paper_2407_20496_amd.build``).
+    Raises if it is missing: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2407_20496_amd.build`; "
+                           "this package has no CPU or PyTorch fallback")
+    lib = C.CDLL(_LIB_PATH)
+    sp = C.POINTER(_Shape)
+    szp = C.POINTER(C.c_size_t)
+    lib.hinm_pack_sizes.argtypes = [sp, szp, szp, szp, szp]
+    lib.hinm_pack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.hinm_unpack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.hinm_spmm.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                              C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_uint32, C.c_void_p, C.c_size_t,
+                              C.c_void_p]
+    lib.hinm_chain_sizes.argtypes = [C.c_int32, C.POINTER(_Layer), C.c_int32, szp]
+    lib.hinm_chain.argtypes = [C.c_int32, C.POINTER(_Layer), C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
+                               C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain"):
+        getattr(lib, name).restype = C.c_int
+    lib.hinm_status_str.argtypes = [C.c_int]
+    lib.hinm_status_str.restype = C.c_char_p
+    lib.hinm_version.argtypes = []
+    lib.hinm_version.restype = C.c_int32
+    _lib = lib
+    return lib
+
+
+def hinm_status_str(status: int) -> str:
+    return load_library().hinm_status_str(int(status)).decode()
+
+
+def hinm_version() -> int:
+    return int(load_library().hinm_version())
+
+
+def _dtype_code(dtype) -> int:
+    if dtype in (F16, "f16"):
+        return F16
+    if dtype in (BF16, "bf16"):
+        return BF16
+    try:
+        import torch
+        if dtype == torch.float16:
+            return F16
+        if dtype == torch.bfloat16:
+            return BF16
+    except ImportError:  # pragma: no cover
+        pass
+    raise ValueError(f"dtype must be f16 or bf16, got {dtype!r}")
+
+
+def _shape(M, K, V, Kv, dtype) -> _Shape:
+    return _Shape(int(M), int(K), int(V), int(Kv), _dtype_code(dtype))
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or raw integer) pointer of a tensor; None stays NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        if torch.cuda.is_available():
+            return torch.cuda.current_stream().cuda_stream or None
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise HinmError(status, where)
+
+
+def hinm_pack_sizes(M, K, V, Kv, dtype) -> Tuple[int, int, int, int]:
+    """(vals_bytes, nm_bytes, vec_bytes, workspace_bytes)."""
+    lib = load_library()
+    out = [C.c_size_t(0) for _ in range(4)]
+    _check(lib.hinm_pack_sizes(C.byref(_shape(M, K, V, Kv, dtype)), *[C.byref(o) for o in out]), "hinm_pack_sizes")
+    return tuple(int(o.value) for o in out)
+
+
+def hinm_pack(M, K, V, Kv, dtype, W, vals, nm_idx, vec_idx, workspace, workspace_bytes, stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_pack(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(vals), _ptr(nm_idx), _ptr(vec_idx),
+                         _ptr(workspace), int(workspace_bytes), _stream(stream)), "hinm_pack")
+
+
+def hinm_unpack(M, K, V, Kv, dtype, vals, nm_idx, vec_idx, W_out, stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_unpack(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(vals), _ptr(nm_idx), _ptr(vec_idx),
+                           _ptr(W_out), _stream(stream)), "hinm_unpack")
+
+
+def hinm_spmm(M, K, V, Kv, dtype, N, vals, nm_idx, vec_idx, pi_in, pi_out, X, ldx, Y, ldy, flags=0,
+              workspace=None, workspace_bytes=0, stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_spmm(C.byref(_shape(M, K, V, Kv, dtype)), int(N), _ptr(vals), _ptr(nm_idx), _ptr(vec_idx),
+                         _ptr(pi_in), _ptr(pi_out), _ptr(X), int(ldx), _ptr(Y), int(ldy), int(flags),
+                         _ptr(workspace), int(workspace_bytes), _stream(stream)), "hinm_spmm")
+
+
+@dataclass
+class Layer:
+    M: int
+    K: int
+    V: int
+    Kv: int
+    dtype: object
+    vals: object
+    nm_idx: object
+    vec_idx: object
+    pi_in: object = None
+    pi_out: object = None
+    flags: int = 0
+
+
+def _layers(layers: Sequence[Layer]):
+    arr = (_Layer * len(layers))()
+    for i, l in enumerate(layers):
+        arr[i] = _Layer(_shape(l.M, l.K, l.V, l.Kv, l.dtype), _ptr(l.vals), _ptr(l.nm_idx), _ptr(l.vec_idx),
+                        _ptr(l.pi_in), _ptr(l.pi_out), int(l.flags))
+    return arr
+
+
+def hinm_chain_sizes(layers: Sequence[Layer], N: int) -> int:
+    lib = load_library()
+    out = C.c_size_t(0)
+    _check(lib.hinm_chain_sizes(len(layers), _layers(layers), int(N), C.byref(out)), "hinm_chain_sizes")
+    return int(out.value)
+
+
+def hinm_chain(layers: Sequence[Layer], N, X, ldx, Y, ldy, scratch, scratch_bytes, stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_chain(len(layers), _layers(layers), int(N), _ptr(X), int(ldx), _ptr(Y), int(ldy),
+                          _ptr(scratch), int(scratch_bytes), _stream(stream)), "hinm_chain")

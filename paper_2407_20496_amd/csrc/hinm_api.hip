@@ -1,0 +1,190 @@
+// C-ABI entry points of libhinm: host-side argument validation and kernel dispatch.
+// Every check here runs before anything is launched, so the error paths need no GPU.
+#include "hinm_internal.h"
+
+namespace {
+
+using namespace hinm;
+
+hinm_status check_shape(const hinm_shape* s) {
+  if (!s) return HINM_ERR_NULL;
+  if (s->dtype != HINM_F16 && s->dtype != HINM_BF16) return HINM_ERR_DTYPE;
+  if (s->M <= 0 || s->K <= 0 || s->V <= 0 || s->Kv <= 0) return HINM_ERR_SHAPE;
+  if (s->M % s->V != 0) return HINM_ERR_SHAPE;
+  if (s->Kv > s->K || s->Kv % 8 != 0) return HINM_ERR_SHAPE;
+  return HINM_OK;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+hinm_status check_spmm(const hinm_shape* s, int32_t N, const void* vals, const uint8_t* nm_idx,
+                       const int32_t* vec_idx, const void* X, int64_t ldx, const void* Y, int64_t ldy,
+                       uint32_t flags) {
+  hinm_status st = check_shape(s);
+  if (st != HINM_OK) return st;
+  if (!vals || !nm_idx || !vec_idx || !X || !Y) return HINM_ERR_NULL;
+  if (N <= 0 || ldx < N || ldy < N) return HINM_ERR_SHAPE;
+  if (N > 1 && (ldx % 8 != 0 || ldy % 8 != 0)) return HINM_ERR_SHAPE;
+  if (!aligned(vals, 16) || !aligned(X, 16) || !aligned(Y, 16)) return HINM_ERR_SHAPE;
+  const uint32_t known = HINM_EPI_RELU | HINM_OUT_F32 | HINM_KERNEL_REFERENCE | HINM_KERNEL_SMFMAC | HINM_KERNEL_GEMV;
+  if (flags & ~known) return HINM_ERR_UNSUPPORTED;
+  const uint32_t forced = flags & (HINM_KERNEL_REFERENCE | HINM_KERNEL_SMFMAC | HINM_KERNEL_GEMV);
+  if (forced & (forced - 1)) return HINM_ERR_UNSUPPORTED;  // at most one kernel may be forced
+  return HINM_OK;
+}
+
+hinm_status run_spmm(const SpmmArgs& a, uint32_t flags, hipStream_t stream) {
+  hipError_t e;
+  if (flags & HINM_KERNEL_REFERENCE) {
+    e = launch_spmm_reference(a, stream);
+  } else if (flags & HINM_KERNEL_SMFMAC) {
+    if (spmm_tile_supported(a)) e = launch_spmm_tile(a, stream);
+    else if (spmm_skinny_supported(a)) e = launch_spmm_skinny(a, stream);
+    else return HINM_ERR_UNSUPPORTED;
+  } else if (flags & HINM_KERNEL_GEMV) {
+    if (a.N > 16 || !spmm_skinny_supported(a)) return HINM_ERR_UNSUPPORTED;
+    e = launch_spmm_skinny(a, stream);
+  } else {
+    // by shape: few columns -> k-split skinny kernel (bandwidth-bound on the packed weights);
+    // otherwise the tile kernel; shapes neither covers fall back to the plain kernel.
+    if (a.N <= 16 && spmm_skinny_supported(a)) e = launch_spmm_skinny(a, stream);
+    else if (spmm_tile_supported(a)) e = launch_spmm_tile(a, stream);
+    else if (spmm_skinny_supported(a)) e = launch_spmm_skinny(a, stream);
+    else e = launch_spmm_reference(a, stream);
+  }
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
+size_t elem_bytes_out(uint32_t flags) { return (flags & HINM_OUT_F32) ? 4 : 2; }
+
+}  // namespace
+
+extern "C" {
+
+hinm_status hinm_pack_sizes(const hinm_shape* shape, size_t* vals_bytes, size_t* nm_bytes, size_t* vec_bytes,
+                            size_t* workspace_bytes) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  const size_t M = shape->M, K = shape->K, Kv = shape->Kv, T = shape->M / shape->V;
+  if (vals_bytes) *vals_bytes = M * (Kv / 2) * 2;
+  if (nm_bytes) *nm_bytes = M * (Kv / 8);
+  if (vec_bytes) *vec_bytes = T * Kv * sizeof(int32_t);
+  if (workspace_bytes) *workspace_bytes = T * K * sizeof(double);
+  return HINM_OK;
+}
+
+hinm_status hinm_pack(const hinm_shape* shape, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (!W || !vals || !nm_idx || !vec_idx) return HINM_ERR_NULL;
+  size_t need = 0;
+  hinm_pack_sizes(shape, nullptr, nullptr, nullptr, &need);
+  if (!workspace || workspace_bytes < need || !aligned(workspace, 8)) return HINM_ERR_WORKSPACE;
+  if (!aligned(vals, 8) || !aligned(vec_idx, 4) || !aligned(W, 2)) return HINM_ERR_SHAPE;
+  hipError_t e = launch_pack(*shape, W, vals, nm_idx, vec_idx, static_cast<double*>(workspace),
+                             static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
+hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
+                        void* W_out, void* stream) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (!vals || !nm_idx || !vec_idx || !W_out) return HINM_ERR_NULL;
+  hipError_t e = launch_unpack(*shape, vals, nm_idx, vec_idx, W_out, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
+hinm_status hinm_spmm(const hinm_shape* shape, int32_t N, const void* vals, const uint8_t* nm_idx,
+                      const int32_t* vec_idx, const int32_t* pi_in, const int32_t* pi_out, const void* X, int64_t ldx,
+                      void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  hinm_status st = check_spmm(shape, N, vals, nm_idx, vec_idx, X, ldx, Y, ldy, flags);
+  if (st != HINM_OK) return st;
+  SpmmArgs a{*shape, N, vals, nm_idx, vec_idx, pi_in, pi_out, X, ldx, Y, ldy,
+             (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0};
+  return run_spmm(a, flags, static_cast<hipStream_t>(stream));
+}
+
+static hinm_status check_chain(int32_t L, const hinm_layer* layers, int32_t N, size_t* bytes_per_buffer) {
+  if (!layers) return HINM_ERR_NULL;
+  if (L <= 0 || N <= 0) return HINM_ERR_SHAPE;
+  size_t widest = 0;
+  for (int l = 0; l < L; ++l) {
+    hinm_status st = check_shape(&layers[l].shape);
+    if (st != HINM_OK) return st;
+    if (!layers[l].vals || !layers[l].nm_idx || !layers[l].vec_idx) return HINM_ERR_NULL;
+    if (layers[l].shape.dtype != layers[0].shape.dtype) return HINM_ERR_DTYPE;
+    if (l > 0 && layers[l].shape.K != layers[l - 1].shape.M) return HINM_ERR_SHAPE;
+    if (l + 1 < L && (layers[l].flags & HINM_OUT_F32)) return HINM_ERR_UNSUPPORTED;
+    if (l + 1 < L) {
+      const size_t b = (size_t)layers[l].shape.M * (size_t)((N + 7) / 8 * 8) * 2;
+      widest = b > widest ? b : widest;
+    }
+  }
+  *bytes_per_buffer = (widest + 255) / 256 * 256;
+  return HINM_OK;
+}
+
+hinm_status hinm_chain_sizes(int32_t L, const hinm_layer* layers, int32_t N, size_t* scratch_bytes) {
+  if (!scratch_bytes) return HINM_ERR_NULL;
+  size_t per = 0;
+  hinm_status st = check_chain(L, layers, N, &per);
+  if (st != HINM_OK) return st;
+  *scratch_bytes = (L <= 1) ? 0 : (L == 2 ? per : 2 * per);
+  return HINM_OK;
+}
+
+hinm_status hinm_chain(int32_t L, const hinm_layer* layers, int32_t N, const void* X, int64_t ldx, void* Y,
+                       int64_t ldy, void* scratch, size_t scratch_bytes, void* stream) {
+  size_t per = 0;
+  hinm_status st = check_chain(L, layers, N, &per);
+  if (st != HINM_OK) return st;
+  if (!X || !Y) return HINM_ERR_NULL;
+  const size_t need = (L <= 1) ? 0 : (L == 2 ? per : 2 * per);
+  if (need > 0 && (!scratch || scratch_bytes < need || !aligned(scratch, 256))) return HINM_ERR_WORKSPACE;
+  const int64_t ldh = (N + 7) / 8 * 8;
+  // validate every layer's call before launching the first one
+  for (int l = 0; l < L; ++l) {
+    const void* in = (l == 0) ? X : scratch;
+    void* out = (l == L - 1) ? Y : scratch;
+    st = check_spmm(&layers[l].shape, N, layers[l].vals, layers[l].nm_idx, layers[l].vec_idx, in,
+                    l == 0 ? ldx : ldh, out, l == L - 1 ? ldy : ldh, layers[l].flags);
+    if (st != HINM_OK) return st;
+  }
+  char* buf[2] = {static_cast<char*>(scratch), static_cast<char*>(scratch) + per};
+  const void* in = X;
+  int64_t ld_in = ldx;
+  for (int l = 0; l < L; ++l) {
+    const bool last = (l == L - 1);
+    void* out = last ? Y : static_cast<void*>(buf[l & 1]);
+    const int64_t ld_out = last ? ldy : ldh;
+    const hinm_layer& ly = layers[l];
+    SpmmArgs a{ly.shape, N, ly.vals, ly.nm_idx, ly.vec_idx, ly.pi_in, ly.pi_out, in, ld_in, out, ld_out,
+               (ly.flags & HINM_EPI_RELU) != 0, (ly.flags & HINM_OUT_F32) != 0};
+    st = run_spmm(a, ly.flags, static_cast<hipStream_t>(stream));
+    if (st != HINM_OK) return st;
+    in = out;
+    ld_in = ld_out;
+  }
+  return HINM_OK;
+}
+
+const char* hinm_status_str(hinm_status s) {
+  switch (s) {
+    case HINM_OK: return "ok";
+    case HINM_ERR_NULL: return "null pointer argument";
+    case HINM_ERR_SHAPE: return "invalid shape, leading dimension or alignment";
+    case HINM_ERR_DTYPE: return "unsupported dtype";
+    case HINM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case HINM_ERR_UNSUPPORTED: return "request not supported by this build";
+    case HINM_ERR_DEVICE: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+int32_t hinm_version(void) { return 1000 * 0 + 1; }
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Internal declarations shared by the translation units of libhinm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hinm.h"
+
+namespace hinm {
+
+// ---- 16-bit storage helpers (device) ---------------------------------------------------------
+
+// Exact widening of a stored 16-bit pattern to float.
+template <int DT>
+__device__ __forceinline__ float bits_to_float(uint16_t b) {
+  if constexpr (DT == HINM_F16) {
+    return (float)__builtin_bit_cast(_Float16, b);
+  } else {
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+  }
+}
+
+// float -> storage type, round-to-nearest-even.
+template <int DT>
+__device__ __forceinline__ uint16_t float_to_bits(float f) {
+  if constexpr (DT == HINM_F16) {
+    return __builtin_bit_cast(uint16_t, (_Float16)f);
+  } else {
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+  }
+}
+
+// ---- launchers implemented in the kernel translation units -------------------------------------
+// All return hipSuccess or the launch error; all are asynchronous on `stream`.
+
+hipError_t launch_pack(const hinm_shape& s, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                       double* scores, hipStream_t stream);
+hipError_t launch_unpack(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
+                         void* W_out, hipStream_t stream);
+
+struct SpmmArgs {
+  hinm_shape s;
+  int32_t N;
+  const void* vals;
+  const uint8_t* nm_idx;
+  const int32_t* vec_idx;
+  const int32_t* pi_in;
+  const int32_t* pi_out;
+  const void* X;
+  int64_t ldx;
+  void* Y;
+  int64_t ldy;
+  bool relu;
+  bool out_f32;
+};
+
+hipError_t launch_spmm_reference(const SpmmArgs& a, hipStream_t stream);
+// Sparse-MFMA tile kernel (32x32x32 form): V in {32, 64, 96, 128}, N >= 1, ldx % 8 == 0, ldy % 8 == 0.
+bool spmm_tile_supported(const SpmmArgs& a);
+hipError_t launch_spmm_tile(const SpmmArgs& a, hipStream_t stream);
+// Sparse-MFMA skinny kernel (16x16x64 form, 16-column blocks, k split over the waves of a workgroup):
+// V % 16 == 0.
+bool spmm_skinny_supported(const SpmmArgs& a);
+hipError_t launch_spmm_skinny(const SpmmArgs& a, hipStream_t stream);
+
+}  // namespace hinm

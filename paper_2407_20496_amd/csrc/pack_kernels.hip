@@ -1,0 +1,257 @@
+// HiNM compression on the GPU (arXiv 2407.20496, Section 1 / Figure 1 walk-through and
+// Section 3.1): column-vector pruning per tile of V rows, then 2:4 on the surviving columns.
+//
+// Three passes over device memory:
+//   score  : s[t][k] = sum_i W[tV+i][k]^2 in binary64, rows added in ascending order
+//   select : per tile, the Kv largest scores (equal scores: lower column first), written as the
+//            ascending vector index
+//   emit   : per row and group of four surviving columns, the two largest magnitudes (equal:
+//            lower position first) -> packed values + NM nibble
+// plus the inverse (unpack) used by the round-trip checks.
+#include "hinm_internal.h"
+
+namespace hinm {
+namespace {
+
+constexpr int kScoreThreads = 256;
+constexpr int kSelectThreads = 1024;
+constexpr int kEmitThreads = 256;
+
+// ---------------------------------------------------------------------------------------------
+// score: one thread owns VEC adjacent columns of one tile and walks down the V rows.
+// The products are exact in binary64 (both factors carry at most 11 significand bits), so the
+// fused multiply-add rounds exactly like a separate add would; only the add order matters and
+// it is fixed to ascending rows.
+// ---------------------------------------------------------------------------------------------
+template <int DT, int VEC>
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(const uint16_t* __restrict__ W,
+                                                              double* __restrict__ scores, int K, int V) {
+  const int t = blockIdx.y;
+  const int64_t c0 = ((int64_t)blockIdx.x * kScoreThreads + threadIdx.x) * VEC;
+  if (c0 >= K) return;
+  const uint16_t* p = W + (size_t)t * V * K + c0;
+  double s[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) s[e] = 0.0;
+  for (int i = 0; i < V; ++i) {
+    uint16_t w[VEC];
+    if constexpr (VEC == 8) {
+      const uint4 q = *reinterpret_cast<const uint4*>(p);
+      w[0] = q.x & 0xFFFF; w[1] = q.x >> 16; w[2] = q.y & 0xFFFF; w[3] = q.y >> 16;
+      w[4] = q.z & 0xFFFF; w[5] = q.z >> 16; w[6] = q.w & 0xFFFF; w[7] = q.w >> 16;
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) w[e] = p[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const double a = (double)bits_to_float<DT>(w[e]);
+      s[e] = __builtin_fma(a, a, s[e]);
+    }
+    p += K;
+  }
+  double* out = scores + (size_t)t * K + c0;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) out[e] = s[e];
+}
+
+// ---------------------------------------------------------------------------------------------
+// select: one workgroup per tile.  Scores are non-negative doubles, so their bit patterns order
+// like unsigned 64-bit integers.  An 8-bit-digit radix descent finds the Kv-th largest key tau and
+// how many keys equal to tau still have to be taken; those are taken from the lowest columns.
+// A final in-order sweep with workgroup prefix sums writes the kept columns ascending.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t block_exclusive_count(bool flag, uint32_t* wave_tot, uint32_t& total) {
+  const unsigned long long bal = __ballot(flag);
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const uint32_t in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+  __syncthreads();  // previous use of wave_tot is over
+  if (lane == 0) wave_tot[wave] = __popcll(bal);
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+  for (int w = 0; w < kSelectThreads / 64; ++w) {
+    const uint32_t c = wave_tot[w];
+    if (w < wave) before += c;
+    all += c;
+  }
+  total = all;
+  return before + in_wave;
+}
+
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __restrict__ scores,
+                                                                int32_t* __restrict__ vec_idx, int K, int Kv) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t wave_tot[kSelectThreads / 64];
+  __shared__ unsigned long long s_prefix;
+  __shared__ uint32_t s_need;
+  const int t = blockIdx.x;
+  const unsigned long long* key = reinterpret_cast<const unsigned long long*>(scores + (size_t)t * K);
+
+  unsigned long long prefix = 0, mask = 0;
+  uint32_t need = (uint32_t)Kv;  // the need-th largest among keys that match prefix under mask
+  for (int shift = 56; shift >= 0; shift -= 8) {
+    if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int k = threadIdx.x; k < K; k += kSelectThreads) {
+      const unsigned long long u = key[k];
+      if ((u & mask) == prefix) atomicAdd(&hist[(uint32_t)(u >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t cum = 0;
+      int d = 255;
+      for (; d > 0; --d) {
+        const uint32_t h = hist[d];
+        if (cum + h >= need) break;
+        cum += h;
+      }
+      s_prefix = prefix | ((unsigned long long)d << shift);
+      s_need = need - cum;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    need = s_need;
+    mask |= 0xFFull << shift;
+  }
+  const unsigned long long tau = prefix;  // Kv-th largest key
+  const uint32_t take_equal = need;       // keys equal to tau that survive (lowest columns)
+
+  uint32_t eq_base = 0, kept_base = 0;
+  int32_t* out = vec_idx + (size_t)t * Kv;
+  for (int k0 = 0; k0 < K; k0 += kSelectThreads) {
+    const int k = k0 + threadIdx.x;
+    const bool in = k < K;
+    const unsigned long long u = in ? key[k] : 0ull;
+    const bool gt = in && u > tau;
+    const bool eq = in && u == tau;
+    uint32_t eq_total, kept_total;
+    const uint32_t eq_rank = eq_base + block_exclusive_count(eq, wave_tot, eq_total);
+    const bool keep = gt || (eq && eq_rank < take_equal);
+    const uint32_t pos = kept_base + block_exclusive_count(keep, wave_tot, kept_total);
+    if (keep) out[pos] = k;
+    eq_base += eq_total;
+    kept_base += kept_total;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// emit: one thread per (row, NM byte) = two groups of four surviving columns.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void top2_of_4(const uint16_t w[4], uint32_t& p0, uint32_t& p1) {
+  uint32_t m[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) m[q] = w[q] & 0x7FFFu;
+  uint32_t kept_mask = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    uint32_t rank = 0;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+      if (o == q) continue;
+      rank += (m[o] > m[q] || (m[o] == m[q] && o < q)) ? 1u : 0u;
+    }
+    if (rank < 2) kept_mask |= 1u << q;
+  }
+  p0 = __builtin_ctz(kept_mask);
+  p1 = 31 - __builtin_clz(kept_mask);
+}
+
+__global__ __launch_bounds__(kEmitThreads) void emit_kernel(const uint16_t* __restrict__ W,
+                                                            const int32_t* __restrict__ vec_idx,
+                                                            uint16_t* __restrict__ vals, uint8_t* __restrict__ nm_idx,
+                                                            int M, int K, int V, int Kv) {
+  const int bytes_per_row = Kv / 8;
+  const int64_t id = (int64_t)blockIdx.x * kEmitThreads + threadIdx.x;
+  if (id >= (int64_t)M * bytes_per_row) return;
+  const int r = (int)(id / bytes_per_row);
+  const int b = (int)(id % bytes_per_row);
+  const int t = r / V;
+  const int32_t* vi = vec_idx + (size_t)t * Kv + 8 * b;
+  const uint16_t* wr = W + (size_t)r * K;
+  uint16_t out[4];
+  uint32_t byte = 0;
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    uint16_t w[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) w[q] = wr[vi[4 * g + q]];
+    uint32_t p0, p1;
+    top2_of_4(w, p0, p1);
+    out[2 * g] = w[p0];
+    out[2 * g + 1] = w[p1];
+    byte |= (p0 | (p1 << 2)) << (4 * g);
+  }
+  uint2 packed;
+  packed.x = (uint32_t)out[0] | ((uint32_t)out[1] << 16);
+  packed.y = (uint32_t)out[2] | ((uint32_t)out[3] << 16);
+  *reinterpret_cast<uint2*>(vals + (size_t)r * (Kv / 2) + 4 * b) = packed;
+  nm_idx[(size_t)r * bytes_per_row + b] = (uint8_t)byte;
+}
+
+// ---------------------------------------------------------------------------------------------
+// unpack: zero fill, then scatter the two survivors of every group.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zero_kernel(uint16_t* __restrict__ p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+__global__ __launch_bounds__(256) void scatter_kernel(const uint16_t* __restrict__ vals,
+                                                      const uint8_t* __restrict__ nm_idx,
+                                                      const int32_t* __restrict__ vec_idx,
+                                                      uint16_t* __restrict__ W, int M, int K, int V, int Kv) {
+  const int groups = Kv / 4;
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (int64_t)M * groups) return;
+  const int r = (int)(id / groups);
+  const int g = (int)(id % groups);
+  const int t = r / V;
+  const uint32_t nib = (nm_idx[(size_t)r * (Kv / 8) + (g >> 1)] >> (4 * (g & 1))) & 0xFu;
+  const int32_t* vi = vec_idx + (size_t)t * Kv + 4 * g;
+  uint16_t* wr = W + (size_t)r * K;
+  wr[vi[nib & 3u]] = vals[(size_t)r * (Kv / 2) + 2 * g];
+  wr[vi[(nib >> 2) & 3u]] = vals[(size_t)r * (Kv / 2) + 2 * g + 1];
+}
+
+}  // namespace
+
+hipError_t launch_pack(const hinm_shape& s, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                       double* scores, hipStream_t stream) {
+  const int T = s.M / s.V;
+  const uint16_t* Wb = static_cast<const uint16_t*>(W);
+  const bool vec8 = (s.K % 8 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15u) == 0);
+  const int cols_per_thread = vec8 ? 8 : 1;
+  const int threads_needed = (s.K + cols_per_thread - 1) / cols_per_thread;
+  dim3 grid((threads_needed + kScoreThreads - 1) / kScoreThreads, T);
+  if (s.dtype == HINM_F16) {
+    if (vec8) score_kernel<HINM_F16, 8><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
+    else score_kernel<HINM_F16, 1><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
+  } else {
+    if (vec8) score_kernel<HINM_BF16, 8><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
+    else score_kernel<HINM_BF16, 1><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  select_kernel<<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t emit_threads = (int64_t)s.M * (s.Kv / 8);
+  emit_kernel<<<(unsigned)((emit_threads + kEmitThreads - 1) / kEmitThreads), kEmitThreads, 0, stream>>>(
+      Wb, vec_idx, static_cast<uint16_t*>(vals), nm_idx, s.M, s.K, s.V, s.Kv);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
+                         void* W_out, hipStream_t stream) {
+  const int64_t n = (int64_t)s.M * s.K;
+  zero_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(static_cast<uint16_t*>(W_out), n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t groups = (int64_t)s.M * (s.Kv / 4);
+  scatter_kernel<<<(unsigned)((groups + 255) / 256), 256, 0, stream>>>(
+      static_cast<const uint16_t*>(vals), nm_idx, vec_idx, static_cast<uint16_t*>(W_out), s.M, s.K, s.V, s.Kv);
+  return hipGetLastError();
+}
+
+}  // namespace hinm

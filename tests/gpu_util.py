@@ -1,0 +1,97 @@
+"""Helpers for the GPU parity tests: move bit-pattern arrays to the device, call
+the library through its C ABI binding, bring results back.  No arithmetic of
+the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2407_20496_amd as hinm
+
+DEV = "cuda:0"
+
+
+def dev_bits(a: np.ndarray) -> torch.Tensor:
+    """uint16 bit patterns -> int16 device tensor (same bits)."""
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(DEV)
+
+
+def dev_i32(a) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def host_bits(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint16)
+
+
+class Packed:
+    def __init__(self, M, K, V, Kv, dtype, vals, nm_idx, vec_idx):
+        self.M, self.K, self.V, self.Kv, self.dtype = M, K, V, Kv, dtype
+        self.vals, self.nm_idx, self.vec_idx = vals, nm_idx, vec_idx
+
+    def host(self):
+        return (host_bits(self.vals).reshape(self.M, self.Kv // 2),
+                self.nm_idx.cpu().numpy().reshape(self.M, self.Kv // 8),
+                self.vec_idx.cpu().numpy().reshape(self.M // self.V, self.Kv))
+
+
+def gpu_pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, W_dev=None) -> Packed:
+    M, K = W_bits.shape
+    vb, nb, cb, wb = hinm.hinm_pack_sizes(M, K, V, Kv, dtype)
+    Wd = dev_bits(W_bits) if W_dev is None else W_dev
+    vals = torch.empty(vb // 2, dtype=torch.int16, device=DEV)
+    nm = torch.empty(nb, dtype=torch.uint8, device=DEV)
+    vec = torch.empty(cb // 4, dtype=torch.int32, device=DEV)
+    ws = torch.empty(wb // 8, dtype=torch.float64, device=DEV)
+    hinm.hinm_pack(M, K, V, Kv, dtype, Wd, vals, nm, vec, ws, wb)
+    torch.cuda.synchronize()
+    return Packed(M, K, V, Kv, dtype, vals, nm, vec)
+
+
+def upload_packed(M, K, V, Kv, dtype, vals, nm_idx, vec_idx) -> Packed:
+    return Packed(M, K, V, Kv, dtype, dev_bits(vals), torch.from_numpy(np.ascontiguousarray(nm_idx)).to(DEV),
+                  dev_i32(vec_idx))
+
+
+def gpu_unpack(p: Packed) -> np.ndarray:
+    W = torch.full((p.M, p.K), 0x7B7B, dtype=torch.int16, device=DEV)   # poison: must be overwritten
+    hinm.hinm_unpack(p.M, p.K, p.V, p.Kv, p.dtype, p.vals, p.nm_idx, p.vec_idx, W)
+    torch.cuda.synchronize()
+    return host_bits(W)
+
+
+def gpu_spmm(p: Packed, X_bits: np.ndarray, pi_in, pi_out, flags=0, ldx=None, ldy=None, X_dev=None):
+    """Returns uint16 bits [M, N], or float32 [M, N] with OUT_F32."""
+    K, N = X_bits.shape
+    ldx = ldx or (N if N == 1 else (N + 7) // 8 * 8)
+    ldy = ldy or (N if N == 1 else (N + 7) // 8 * 8)
+    if X_dev is None:
+        Xp = np.zeros((K, ldx), dtype=np.uint16)
+        Xp[:, :N] = X_bits
+        X_dev = dev_bits(Xp)
+    f32 = bool(flags & hinm.OUT_F32)
+    if f32:
+        Y = torch.full((p.M, ldy), float("nan"), dtype=torch.float32, device=DEV)
+    else:
+        Y = torch.full((p.M, ldy), 0x7B7B, dtype=torch.int16, device=DEV)
+    hinm.hinm_spmm(p.M, p.K, p.V, p.Kv, p.dtype, N, p.vals, p.nm_idx, p.vec_idx,
+                   None if pi_in is None else dev_i32(pi_in), None if pi_out is None else dev_i32(pi_out),
+                   X_dev, ldx, Y, ldy, flags)
+    torch.cuda.synchronize()
+    if f32:
+        out = Y.cpu().numpy()
+        pad = out[:, N:]
+        assert np.all(np.isnan(pad)), "columns beyond N were written"
+        return out[:, :N].copy()
+    out = host_bits(Y)
+    assert np.all(out[:, N:] == 0x7B7B), "columns beyond N were written"
+    return out[:, :N].copy()
+
+
+def check_close(got_f64: np.ndarray, want_f64: np.ndarray, rel_fro=1e-3, max_abs=1e-2, what=""):
+    """The tolerance the benchmark spec states: relative Frobenius error and max abs error."""
+    diff = got_f64 - want_f64
+    fro = np.linalg.norm(diff) / max(np.linalg.norm(want_f64), 1e-30)
+    mx = np.abs(diff).max() if diff.size else 0.0
+    assert fro <= rel_fro and mx <= max_abs, f"{what}: rel-Fro {fro:.3e} (<= {rel_fro}), max-abs {mx:.3e} (<= {max_abs})"
+    return fro, mx

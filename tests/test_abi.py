@@ -1,0 +1,105 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every declared entry point, computes sizes, and rejects bad arguments before
+launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2407_20496_amd as hinm
+from paper_2407_20496_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hinm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hinm_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = hinm.load_library()
+    names = declared_functions()
+    assert set(names) == set(hinm.exported_symbols())
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert hinm.hinm_version() >= 1
+    assert hinm.hinm_status_str(0) == "ok"
+    for s in range(1, 7):
+        assert hinm.hinm_status_str(s) not in ("ok", "unknown status")
+
+
+def test_pack_sizes():
+    v, n, c, w = hinm.hinm_pack_sizes(3072, 768, 64, 384, "f16")
+    assert (v, n, c, w) == (3072 * 192 * 2, 3072 * 48, 48 * 384 * 4, 48 * 768 * 8)
+
+
+@pytest.mark.parametrize("M,K,V,Kv,dtype,status", [
+    (256, 256, 17, 128, 0, 2),    # M % V != 0
+    (256, 256, 16, 132, 0, 2),    # Kv % 8 != 0
+    (256, 256, 16, 264, 0, 2),    # Kv > K
+    (0, 256, 16, 128, 0, 2),
+    (256, 256, 16, 128, 7, 3),    # dtype
+])
+def test_shape_errors(M, K, V, Kv, dtype, status):
+    lib = hinm.load_library()
+    sh = binding._Shape(M, K, V, Kv, dtype)
+    out = C.c_size_t(0)
+    assert lib.hinm_pack_sizes(C.byref(sh), C.byref(out), None, None, None) == status
+
+
+def test_null_and_workspace_errors_are_reported_before_any_launch():
+    lib = hinm.load_library()
+    sh = binding._Shape(256, 256, 16, 128, 0)
+    fake = 0x1000  # never dereferenced: validation fails first
+    assert lib.hinm_pack(C.byref(sh), None, fake, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.hinm_pack(C.byref(sh), fake, fake, fake, fake, None, 0, None) == 4
+    assert lib.hinm_pack(C.byref(sh), fake, fake, fake, fake, fake, 16, None) == 4      # too small
+    assert lib.hinm_unpack(C.byref(sh), fake, fake, None, fake, None) == 1
+    # spmm: null X, bad N, bad ld, misaligned X, unknown flag, two kernels forced
+    args = dict(N=64, vals=fake, nm=fake, vec=fake, X=fake, ldx=64, Y=fake, ldy=64, flags=0)
+
+    def call(**kw):
+        a = dict(args, **kw)
+        return lib.hinm_spmm(C.byref(sh), a["N"], a["vals"], a["nm"], a["vec"], None, None, a["X"], a["ldx"],
+                             a["Y"], a["ldy"], a["flags"], None, 0, None)
+    assert call(X=None) == 1
+    assert call(N=0) == 2
+    assert call(ldx=60) == 2
+    assert call(ldx=68) == 2            # not a multiple of 8
+    assert call(X=fake + 2) == 2
+    assert call(flags=0x8000) == 5
+    assert call(flags=0x300) == 5
+
+
+def test_chain_validation():
+    lib = hinm.load_library()
+    fake = 0x1000
+    mk = lambda M, K, dtype=0, flags=0: binding._Layer(binding._Shape(M, K, 16, K // 2, dtype), fake, fake, fake,
+                                                       None, None, flags)
+    out = C.c_size_t(0)
+    two = (binding._Layer * 2)(mk(256, 128), mk(64, 256))
+    assert lib.hinm_chain_sizes(2, two, 100, C.byref(out)) == 0
+    assert out.value == 256 * 104 * 2           # one intermediate, columns padded to 8
+    three = (binding._Layer * 3)(mk(256, 128), mk(64, 256), mk(32, 64))
+    assert lib.hinm_chain_sizes(3, three, 8, C.byref(out)) == 0
+    assert out.value == 2 * 256 * 8 * 2
+    bad = (binding._Layer * 2)(mk(256, 128), mk(64, 128))          # K of layer 2 != M of layer 1
+    assert lib.hinm_chain_sizes(2, bad, 8, C.byref(out)) == 2
+    bad = (binding._Layer * 2)(mk(256, 128), mk(64, 256, dtype=1))  # mixed dtypes
+    assert lib.hinm_chain_sizes(2, bad, 8, C.byref(out)) == 3
+    bad = (binding._Layer * 2)(mk(256, 128, flags=2), mk(64, 256))  # fp32 output before the last layer
+    assert lib.hinm_chain_sizes(2, bad, 8, C.byref(out)) == 5
+    assert lib.hinm_chain(2, two, 8, fake, 8, fake, 8, None, 0, None) == 4   # scratch missing
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libhinm.so"))
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        binding.hinm_pack_sizes(256, 256, 16, 128, "f16")

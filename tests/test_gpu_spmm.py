@@ -1,0 +1,213 @@
+"""GPU parity of hinm_spmm / hinm_chain against the CPU oracle.
+
+Tolerance (from the benchmark spec): relative Frobenius error <= 1e-3 and
+max abs error <= 1e-2 on unit-scale inputs with fp32 accumulation.  fp16
+outputs meet it literally against the oracle's un-rounded product.  For bf16
+the rounding of the output alone exceeds it (one bf16 ulp is 0.0156 for
+2 <= |y| < 4), so bf16 cases are checked twice: the fp32 accumulators
+(HINM_OUT_F32) against the literal thresholds, and the bf16 output against the
+oracle rounded to bf16 with |diff| <= max(1e-2, 1 ulp) and rel-Fro <= 1e-3.
+"""
+import numpy as np
+import pytest
+
+import hinm_synth as synth
+from oracle import hinm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+REF, SMFMAC, GEMV = 0x100, 0x200, 0x400
+OUT_F32, RELU = 2, 1
+
+
+def _ulp(y, dtype):
+    mant = 7 if dtype == "bf16" else 10
+    e = np.floor(np.log2(np.maximum(np.abs(y), 2.0 ** -14)))
+    return np.exp2(e - mant)
+
+
+def _oracle_pack(case, layer=0):
+    Wb = case.weights(layer)
+    vals, nm, vec = orc.pack(Wb, case.dtype, case.V, case.Kv)
+    Wh = orc.unpack_fast(vals, nm, vec, case.M, case.K, case.V)
+    return vals, nm, vec, Wh
+
+
+def _check_full(case, N, flags_list, relu=False, identity=False, ld_pad=0):
+    """Compare every output element with the oracle's matrix-form product."""
+    from tests import gpu_util as gu
+    vals, nm, vec, Wh = _oracle_pack(case)
+    Xb = case.activations(N)
+    pi_in = None if identity else case.pi_in()
+    pi_out = None if identity else case.pi_out()
+    Y_acc = orc.product(Wh, Xb, case.dtype, pi_in, pi_out, acc=np.float32, relu=relu).astype(np.float64)
+    Y_bits = orc.round_to_storage(Y_acc.astype(np.float32), case.dtype)
+    p = gu.upload_packed(case.M, case.K, case.V, case.Kv, case.dtype, vals, nm, vec)
+    ld = None if ld_pad == 0 else (N + 7) // 8 * 8 + ld_pad
+    for flags in flags_list:
+        f = flags | (RELU if relu else 0)
+        got32 = gu.gpu_spmm(p, Xb, pi_in, pi_out, f | OUT_F32, ldx=ld, ldy=ld).astype(np.float64)
+        gu.check_close(got32, Y_acc, what=f"{case.name} flags {f:#x} fp32 accumulators")
+        got = gu.gpu_spmm(p, Xb, pi_in, pi_out, f, ldx=ld, ldy=ld)
+        gotd = orc.decode(got, case.dtype)
+        if case.dtype == "f16":
+            gu.check_close(gotd, Y_acc, what=f"{case.name} flags {f:#x} fp16 output")
+        else:
+            want = orc.decode(Y_bits, case.dtype)
+            assert np.all(np.abs(gotd - want) <= np.maximum(1e-2, _ulp(want, "bf16"))), f"{case.name} {f:#x}"
+            gu.check_close(gotd, want, max_abs=np.inf, what=f"{case.name} flags {f:#x} bf16 output")
+        # outputs must be the correctly rounded accumulators
+        assert np.array_equal(got, orc.round_to_storage(got32.astype(np.float32), case.dtype))
+
+
+# ---- small multi-tile cases, ragged N, every kernel ------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("M,K,V,Kv,N", [
+    (64, 96, 16, 48, 5),
+    (128, 256, 32, 128, 37),
+    (128, 320, 64, 160, 300),      # N spans two column blocks of the tile kernel with a ragged tail
+    (384, 512, 128, 256, 264),
+    (192, 256, 96, 64, 40),
+    (64, 200, 16, 72, 19),         # Kv % 64 != 0: k tail
+])
+def test_spmm_small_all_kernels(M, K, V, Kv, N, dtype):
+    case = synth.small_case(M, K, V, Kv, N, dtype, 60)
+    flags = [REF, 0]
+    if V % 32 == 0 and Kv % 32 == 0:
+        flags.append(SMFMAC)
+    if N <= 16:
+        flags.append(GEMV)
+    _check_full(case, N, flags)
+
+
+def test_spmm_relu_identity_and_padded_leading_dimensions():
+    case = synth.small_case(128, 256, 64, 128, 72, "f16", 61)
+    _check_full(case, 72, [REF, SMFMAC], relu=True)
+    _check_full(case, 72, [REF, SMFMAC], identity=True)
+    _check_full(case, 72, [REF, SMFMAC], ld_pad=24)
+    case = synth.small_case(64, 128, 16, 64, 3, "bf16", 62)
+    _check_full(case, 3, [REF, GEMV], relu=True, ld_pad=8)
+    _check_full(case, 1, [REF, GEMV, 0])
+
+
+def test_spmm_tile_order_invariance_on_gpu():
+    # Section 3.2: re-ordering whole groups inside a tile must not change the product
+    from tests import gpu_util as gu
+    case = synth.small_case(128, 256, 64, 128, 64, "f16", 63)
+    vals, nm, vec, Wh = _oracle_pack(case)
+    rng = np.random.default_rng(2)
+    G = case.Kv // 4
+    nib = np.stack([nm & 0xF, nm >> 4], axis=-1).reshape(case.M, G)
+    vals2, vec2, nib2 = vals.copy(), vec.copy(), nib.copy()
+    for t in range(case.T):
+        perm = rng.permutation(G)
+        rows = slice(t * case.V, (t + 1) * case.V)
+        vec2[t] = vec[t].reshape(G, 4)[perm].reshape(-1)
+        vals2[rows] = vals[rows].reshape(case.V, G, 2)[:, perm].reshape(case.V, -1)
+        nib2[rows] = nib[rows][:, perm]
+    nm2 = (nib2[:, 0::2] | (nib2[:, 1::2] << 4)).astype(np.uint8)
+    Xb = case.activations()
+    Y = orc.product(Wh, Xb, "f16", case.pi_in(), case.pi_out()).astype(np.float64)
+    p2 = gu.upload_packed(case.M, case.K, case.V, case.Kv, "f16", vals2, nm2, vec2)
+    for flags in (REF, SMFMAC):
+        got = gu.gpu_spmm(p2, Xb, case.pi_in(), case.pi_out(), flags | OUT_F32).astype(np.float64)
+        gu.check_close(got, Y, what="shuffled groups")
+
+
+# ---- the named workloads ---------------------------------------------------------------------
+
+def test_c1_full():
+    c = synth.c1()
+    _check_full(c, c.N, [REF, 0, SMFMAC])
+
+
+def test_c2_full():
+    c = synth.c2()
+    _check_full(c, c.N, [0])
+
+
+def _check_sampled(case, N, n_rows=24, n_cols=64, X_dev=None):
+    """Full-size layers: sampled outputs computed one by one by the oracle, plus
+    the whole-matrix agreement of the fast kernel with the plain GPU kernel on a
+    column slice is covered by the small cases; here rows are drawn from the first,
+    a middle and the last tile and columns from every column block."""
+    from tests import gpu_util as gu
+    Wb = case.weights()
+    p = gu.gpu_pack(Wb, case.dtype, case.V, case.Kv)
+    vals, nm, vec = p.host()
+    rng = np.random.default_rng(case.M + N)
+    tiles = [0, case.T // 2, case.T - 1]
+    rows = np.concatenate([t * case.V + rng.choice(case.V, n_rows // 3, replace=False) for t in tiles])
+    o_vals, o_nm, o_vec = [], [], []
+    Wh_rows = np.zeros((len(rows), case.K), dtype=np.uint16)
+    for t in tiles:
+        sl = slice(t * case.V, (t + 1) * case.V)
+        ov, on, oc = orc.pack(Wb[sl], case.dtype, case.V, case.Kv)
+        assert np.array_equal(vec[t], oc[0]) and np.array_equal(vals[sl], ov) and np.array_equal(nm[sl], on)
+        Wh_t = orc.unpack_fast(ov, on, oc, case.V, case.K, case.V)
+        for a, r in enumerate(rows):
+            if r // case.V == t:
+                Wh_rows[a] = Wh_t[r - t * case.V]
+    Xb = case.activations(N)
+    cols = np.unique(np.concatenate([[0, N - 1], rng.choice(N, min(N, n_cols), replace=False)]))
+    pi_in, pi_out = case.pi_in(), case.pi_out()
+    want = orc.product_entries(Wh_rows, Xb, case.dtype, pi_in, None, np.arange(len(rows)), cols)
+    got32 = gu.gpu_spmm(p, Xb, pi_in, pi_out, OUT_F32, X_dev=X_dev)
+    sub = got32[pi_out[rows]][:, cols].astype(np.float64)
+    gu.check_close(sub, want, what=f"{case.name} sampled fp32 accumulators")
+    got = gu.gpu_spmm(p, Xb, pi_in, pi_out, 0, X_dev=X_dev)
+    assert np.array_equal(got, orc.round_to_storage(got32, case.dtype)), "output is not the rounded accumulator"
+    # property that holds at any size: every output row was written exactly once (poison gone, no NaN)
+    assert np.isfinite(got32).all()
+    return got32
+
+
+@pytest.mark.parametrize("idx", range(12))
+def test_c3_sampled(idx):
+    c = synth.c3_cases()[idx]
+    _check_sampled(c, c.N)
+
+
+def test_c4_chain_full():
+    from tests import gpu_util as gu
+    import paper_2407_20496_amd as hinm
+    import torch
+    c = synth.c4()
+    layers, host_layers = [], []
+    for l in (0, 1):
+        p = gu.gpu_pack(c.weights(l), c.dtype, c.V, c.Kv)
+        vals, nm, vec = p.host()
+        Wh = orc.unpack_fast(vals, nm, vec, c.M, c.K, c.V)
+        pin, pout = c.pi_in(l), c.pi_out(l)
+        host_layers.append((Wh, pin, pout, l == 0))
+        layers.append(hinm.Layer(c.M, c.K, c.V, c.Kv, c.dtype, p.vals, p.nm_idx, p.vec_idx,
+                                 gu.dev_i32(pin), gu.dev_i32(pout), RELU if l == 0 else 0))
+    Xb = c.activations()
+    want_bits = orc.chain(host_layers, Xb, c.dtype)
+    H = orc.spmm(host_layers[0][0], Xb, c.dtype, host_layers[0][1], host_layers[0][2], relu=True)
+    want_acc = orc.product(host_layers[1][0], H, c.dtype, host_layers[1][1], host_layers[1][2]).astype(np.float64)
+    nbytes = hinm.hinm_chain_sizes(layers, c.N)
+    assert nbytes == c.M * c.N * 2
+    scratch = torch.empty(nbytes, dtype=torch.uint8, device=gu.DEV)
+    Y = torch.empty((c.M, c.N), dtype=torch.int16, device=gu.DEV)
+    hinm.hinm_chain(layers, c.N, gu.dev_bits(Xb), c.N, Y, c.N, scratch, nbytes)
+    torch.cuda.synchronize()
+    got = gu.host_bits(Y)
+    gu.check_close(orc.decode(got, c.dtype), want_acc, what="C4 chain")
+    # the intermediate left in scratch is layer 1's rounded, ReLU-ed, pi_out-ordered output
+    Hg = gu.host_bits(scratch.view(torch.int16).reshape(c.M, c.N))
+    gu.check_close(orc.decode(Hg, c.dtype), orc.decode(H, c.dtype), what="C4 intermediate")
+    assert (orc.decode(Hg, c.dtype) >= 0).all()
+    # same result as two separate hinm_spmm calls
+    p1 = gu.Packed(c.M, c.K, c.V, c.Kv, c.dtype, layers[0].vals, layers[0].nm_idx, layers[0].vec_idx)
+    p2 = gu.Packed(c.M, c.K, c.V, c.Kv, c.dtype, layers[1].vals, layers[1].nm_idx, layers[1].vec_idx)
+    H2 = gu.gpu_spmm(p1, Xb, host_layers[0][1], host_layers[0][2], RELU)
+    Y2 = gu.gpu_spmm(p2, H2, host_layers[1][1], host_layers[1][2], 0)
+    assert np.array_equal(Y2, got)
+    del want_bits
+
+
+def test_c5_sampled():
+    c = synth.c5()
+    _check_sampled(c, c.N, n_rows=12, n_cols=48)
