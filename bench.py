@@ -1,0 +1,306 @@
+#!/usr/bin/env python3
+"""Benchmark of the HiNM sparse-GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+
+A step is one pass of the run-time path (gather through vector index o pi_in,
+sparse-MFMA product, pi_out scatter epilogue: hinm_spmm, or hinm_chain for c4)
+over one batch of synthetic input that is already resident in HBM.  Packing is
+the offline compression step of the method; it is timed by `--workload pack-c5`.
+Consecutive steps rotate over enough independent copies of (packed W, X, Y)
+to exceed the 256 MB Infinity Cache, so the traffic really comes from HBM.
+
+Prints ONE JSON line (see the design doc for the field definitions).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import hinm_synth as synth  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_DENSE_PEAK_TFLOPS = 2500.0   # fp16 / bf16 dense; useful (stored-value) flops are priced against this
+
+
+def workloads():
+    w = {"c1": synth.c1(), "c2": synth.c2(), "c4": synth.c4(), "c5": synth.c5()}
+    for c in synth.c3_cases():
+        keep = "50" if c.Kv * 2 == c.K else "75"
+        w[f"c3-{c.M}x{c.K}-s{keep}-n{c.N}"] = c
+    return w
+
+
+def algorithmic_bytes(c, N, layers=1):
+    """Compulsory HBM traffic of one step: packed values + NM nibbles + vector index (int32) +
+    both permutations + X + Y, each moved once."""
+    per_layer = (c.M * c.Kv // 2 * 2 + c.M * c.Kv // 8 + c.T * c.Kv * 4 + c.K * 4 + c.M * 4
+                 + c.K * N * 2 + c.M * N * 2)
+    return per_layer * layers
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-dense", action="store_true", help="skip the same-shape dense GEMM reference")
+    ap.add_argument("--identity", action="store_true", help="run with identity permutations")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2407_20496_amd as hinm
+    hinm.load_library()  # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    if args.workload == "pack-c5":
+        return bench_pack(args, torch, hinm, dev)
+    wl = workloads()
+    if args.workload not in wl:
+        print("unknown workload; choose from: pack-c5 " + " ".join(wl), file=sys.stderr)
+        sys.exit(2)
+    c = wl[args.workload]
+    chain = args.workload == "c4"
+    N = c.N
+    n_layers = 2 if chain else 1
+
+    def dev_bits(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev)
+
+    # ---- inputs: drawn on the host from the seeded generator, packed on the GPU --------------
+    vb, nb, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+    packed = []
+    for l in range(n_layers):
+        W = dev_bits(c.weights(l))
+        vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
+        nm = torch.empty(nb, dtype=torch.uint8, device=dev)
+        vec = torch.empty(cb // 4, dtype=torch.int32, device=dev)
+        ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
+        hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
+        torch.cuda.synchronize()
+        del ws
+        pin = None if args.identity else torch.from_numpy(c.pi_in(l)).to(dev)
+        pout = None if args.identity else torch.from_numpy(c.pi_out(l)).to(dev)
+        packed.append((W if (l == 0 and not args.no_dense) else None, vals, nm, vec, pin, pout))
+        if not (l == 0 and not args.no_dense):
+            del W
+    ldn = N if N == 1 else (N + 7) // 8 * 8
+    Xh = np.zeros((c.K, ldn), dtype=np.uint16)
+    Xh[:, :N] = c.activations()
+    X0 = dev_bits(Xh)
+
+    bytes_step = algorithmic_bytes(c, N, n_layers)
+    per_set = sum(t.numel() * t.element_size() for (_, v, n, ve, _, _) in packed for t in (v, n, ve)) \
+        + (c.K + c.M) * ldn * 2 * n_layers
+    n_sets = max(2, min(64, int(np.ceil(600e6 / per_set))))
+    sets = []
+    for i in range(n_sets):
+        layers = []
+        for (_, vals, nm, vec, pin, pout) in packed:
+            if i == 0:
+                layers.append((vals, nm, vec, pin, pout))
+            else:
+                layers.append((vals.clone(), nm.clone(), vec.clone(), pin, pout))
+        X = X0 if i == 0 else X0.clone()
+        Y = torch.zeros((c.M, ldn), dtype=torch.int16, device=dev)
+        scratch = torch.empty(c.M * ldn * 2, dtype=torch.uint8, device=dev) if chain else None
+        sets.append((layers, X, Y, scratch))
+
+    def step(i):
+        layers, X, Y, scratch = sets[i % n_sets]
+        if chain:
+            ls = [hinm.Layer(c.M, c.K, c.V, c.Kv, c.dtype, v, n, ve, pi, po, hinm.EPI_RELU if l == 0 else 0)
+                  for l, (v, n, ve, pi, po) in enumerate(layers)]
+            hinm.hinm_chain(ls, N, X, ldn, Y, ldn, scratch, scratch.numel())
+        else:
+            v, n, ve, pi, po = layers[0]
+            hinm.hinm_spmm(c.M, c.K, c.V, c.Kv, c.dtype, N, v, n, ve, pi, po, X, ldn, Y, ldn, 0)
+
+    flops_dense_equiv = 2.0 * c.M * c.K * N * n_layers
+    flops_stored = 2.0 * c.M * (c.Kv // 2) * N * n_layers
+    # pick K so the timed region is long enough to be meaningful but well under a minute
+    step(0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(3):
+        step(i)
+    torch.cuda.synchronize()
+    est = (time.perf_counter() - t0) / 3
+    steps = args.steps if args.steps is not None else int(min(20000, max(50, 2.0 / max(est, 1e-6))))
+    warmup = args.warmup if args.warmup is not None else max(5, steps // 10)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / steps
+    gpu_ms_per_step = ev0.elapsed_time(ev1) / steps
+
+    # ---- per-launch kernel time with HIP events on the launch stream (same rotation) ----------
+    n_ev = min(steps, 200)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for i, (a, b) in enumerate(pairs):
+        a.record()
+        step(i)
+        b.record()
+    torch.cuda.synchronize()
+    per_launch_ms = sorted(a.elapsed_time(b) for a, b in pairs)
+    kernel_ms_avg = float(np.mean(per_launch_ms)) / n_layers
+    kernel_ms_med = float(per_launch_ms[len(per_launch_ms) // 2]) / n_layers
+    # the back-to-back rate bounds the kernel time from above as well; use the smaller of the two
+    kernel_ms = min(kernel_ms_avg, gpu_ms_per_step / n_layers)
+
+    mem_bound = (bytes_step / HBM_PEAK_GBPS / 1e9) >= (flops_stored / MFMA_DENSE_PEAK_TFLOPS / 1e12)
+    if mem_bound:
+        ach = bytes_step / n_layers / (kernel_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None}
+    else:
+        ach = flops_stored / n_layers / (kernel_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / MFMA_DENSE_PEAK_TFLOPS, 4), "traffic": None}
+    roofline["kernel"] = "spmm_skinny_kernel" if N <= 16 or c.V % 32 else "spmm_tile_kernel"
+    roofline["kernel_ms_avg"] = round(kernel_ms, 6)
+    roofline["kernel_ms_median_event_pair"] = round(kernel_ms_med, 6)
+    roofline["algorithmic_bytes_per_launch"] = bytes_step // n_layers
+    roofline["stored_value_flops_per_launch"] = flops_stored / n_layers
+
+    # ---- same-shape dense GEMM (library) on the same tensors, same timing method ---------------
+    dense = None
+    if not args.no_dense and packed[0][0] is not None:
+        tdt = torch.float16 if c.dtype == "f16" else torch.bfloat16
+        Wd = packed[0][0].view(tdt).reshape(c.M, c.K)
+        Xd = X0.view(tdt).reshape(c.K, ldn)[:, :N].contiguous()
+        for _ in range(3):
+            torch.matmul(Wd, Xd)
+        torch.cuda.synchronize()
+        reps = max(5, min(200, steps // 10))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            torch.matmul(Wd, Xd)
+        e1.record()
+        torch.cuda.synchronize()
+        dms = e0.elapsed_time(e1) / reps
+        dense = {"ms": round(dms, 5), "tflops": round(2.0 * c.M * c.K * N / dms / 1e9, 2),
+                 "note": "torch.matmul on the unpruned W, single buffer set (cache-warm)"}
+
+    # ---- CPU oracle baseline on the host cores ---------------------------------------------------
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(c, N, chain)
+
+    value = flops_dense_equiv / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "hinm_spmm_dense_equiv_tflops", "value": round(value, 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c.dtype, "data": "synthetic",
+        "config": {"workload": c.name + (" (two-layer chain)" if chain else ""), "M": c.M, "K": c.K, "V": c.V,
+                   "Kv": c.Kv, "N": N, "layers": n_layers,
+                   "permutation": "identity" if args.identity else "seeded random pi_in/pi_out",
+                   "buffer_sets_rotated": n_sets},
+        "gpu_ms_per_step_events": round(gpu_ms_per_step, 6),
+        "hbm_gbps_algorithmic": round(bytes_step / (gpu_ms_per_step * 1e-3) / 1e9, 1),
+        "stored_value_tflops": round(flops_stored / (gpu_ms_per_step * 1e-3) / 1e12, 3),
+        "roofline": roofline, "cpu_baseline": cpu, "dense_gemm": dense,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(c, N, chain):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload."""
+    from oracle import hinm_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    # bounded sample: at most 8 tiles of W (all their rows) and at most 512 columns of X
+    tiles = min(c.T, 8)
+    rows = tiles * c.V
+    n = min(N, 512)
+    Wb = c.weights()[:rows]
+    t0 = time.perf_counter()
+    vals, nm, vec = orc.pack(Wb, c.dtype, c.V, c.Kv)
+    t_pack = time.perf_counter() - t0
+    Wh = orc.unpack_fast(vals, nm, vec, rows, c.K, c.V)
+    Xb = c.activations()[:, :n]
+    pin = c.pi_in()
+    pout = np.argsort(np.argsort(c.pi_out()[:rows])).astype(np.int32)   # a permutation of the sampled rows
+    reps, t_prod = 0, 0.0
+    while t_prod < 5.0 and reps < 50:
+        t0 = time.perf_counter()
+        orc.spmm(Wh, Xb, c.dtype, pin, pout)
+        t_prod += time.perf_counter() - t0
+        reps += 1
+    t_one = t_prod / reps
+    layers = 2 if chain else 1
+    return {"value": round(2.0 * rows * c.K * n / t_one / 1e12, 5), "unit": "TFLOP/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": f"oracle product (explicit permutation matrices, float32 numpy matmul) on {tiles} of {c.T} "
+                      f"tiles x {n} of {N} columns, {reps} repetitions, {t_one * 1e3:.1f} ms each; "
+                      f"oracle pack of those tiles {t_pack * 1e3:.1f} ms; host cpu_count {os.cpu_count()}"
+                      + ("; one layer of the two" if layers == 2 else "")}
+
+
+def bench_pack(args, torch, hinm, dev):
+    c = synth.c5()
+    W = torch.from_numpy(c.weights().view(np.int16)).to(dev)
+    vb, nb, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+    vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
+    nm = torch.empty(nb, dtype=torch.uint8, device=dev)
+    vec = torch.empty(cb // 4, dtype=torch.int32, device=dev)
+    ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
+    steps = args.steps or 10
+    warmup = args.warmup or 2
+    for _ in range(warmup):
+        hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    ms = e0.elapsed_time(e1) / steps
+    traffic = 2 * c.M * c.K * 2 + vb + nb + cb + 2 * wb   # W read twice, outputs, scores written + read
+    out = {"metric": "hinm_pack_gbps", "value": round(traffic / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": round(wall * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": c.dtype, "data": "synthetic",
+           "config": {"workload": "hinm_pack of " + c.name},
+           "roofline": {"bound": "hbm", "achieved": round(traffic / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                        "unit": "GB/s", "frac": round(traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                        "traffic": None, "algorithmic_bytes_per_launch": traffic},
+           "cpu_baseline": None}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -49,6 +49,10 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2407_20496_amd.build`; "
                            "this package has no CPU or PyTorch fallback")
+    # PyTorch ships its own HIP runtime (same soname as the system one).  It must be in the process
+    # before libhinm.so is opened so that both bind to ONE runtime: with two, streams, events and
+    # device pointers of one are meaningless to the other.
+    import torch  # noqa: F401
     lib = C.CDLL(_LIB_PATH)
     sp = C.POINTER(_Shape)
     szp = C.POINTER(C.c_size_t)
