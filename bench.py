@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the same-shape dense GEMM reference")
     ap.add_argument("--identity", action="store_true", help="run with identity permutations")
+    ap.add_argument("--canonical", action="store_true",
+                    help="call hinm_spmm on the canonical arrays instead of hinm_spmm_prepared")
+    ap.add_argument("--variant", type=int, default=0, help="pin a tile-kernel configuration (tuning aid)")
     ap.add_argument("--sets", type=int, default=None,
                     help="number of rotated buffer sets (default: enough to exceed the Infinity Cache)")
     ap.add_argument("--no-graph", action="store_true",
@@ -88,7 +91,8 @@ def main():
     def dev_bits(a):
         return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev)
 
-    # ---- inputs: drawn on the host from the seeded generator, packed on the GPU --------------
+    use_prepared = (not args.canonical) and c.V % 32 == 0
+    # ---- inputs: drawn on the host from the seeded generator, packed (and prepared) on the GPU ----
     vb, nb, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
     packed = []
     for l in range(n_layers):
@@ -102,7 +106,13 @@ def main():
         del ws
         pin = None if args.identity else torch.from_numpy(c.pi_in(l)).to(dev)
         pout = None if args.identity else torch.from_numpy(c.pi_out(l)).to(dev)
-        packed.append((W if (l == 0 and not args.no_dense) else None, vals, nm, vec, pin, pout))
+        prep = None
+        if use_prepared:
+            pbytes = hinm.hinm_prepare_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+            prep = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+            hinm.hinm_prepare(c.M, c.K, c.V, c.Kv, c.dtype, vals, nm, vec, pin, pout, prep, pbytes)
+            torch.cuda.synchronize()
+        packed.append((W if (l == 0 and not args.no_dense) else None, vals, nm, vec, pin, pout, prep))
         if not (l == 0 and not args.no_dense):
             del W
     ldn = N if N == 1 else (N + 7) // 8 * 8
@@ -111,31 +121,41 @@ def main():
     X0 = dev_bits(Xh)
 
     bytes_step = algorithmic_bytes(c, N, n_layers)
-    per_set = sum(t.numel() * t.element_size() for (_, v, n, ve, _, _) in packed for t in (v, n, ve)) \
+    per_set = sum(t.numel() * t.element_size() for (_, v, n, ve, _, _, _) in packed for t in (v, n, ve)) \
         + (c.K + c.M) * ldn * 2 * n_layers
     n_sets = args.sets if args.sets else max(2, min(64, int(np.ceil(600e6 / per_set))))
     sets = []
     for i in range(n_sets):
         layers = []
-        for (_, vals, nm, vec, pin, pout) in packed:
-            if i == 0:
-                layers.append((vals, nm, vec, pin, pout))
+        for (_, vals, nm, vec, pin, pout, prep) in packed:
+            if use_prepared:
+                layers.append((None, None, None, None, None, prep if i == 0 else prep.clone()))
+            elif i == 0:
+                layers.append((vals, nm, vec, pin, pout, None))
             else:
-                layers.append((vals.clone(), nm.clone(), vec.clone(), pin, pout))
+                layers.append((vals.clone(), nm.clone(), vec.clone(), pin, pout, None))
         X = X0 if i == 0 else X0.clone()
         Y = torch.zeros((c.M, ldn), dtype=torch.int16, device=dev)
         scratch = torch.empty(c.M * ldn * 2, dtype=torch.uint8, device=dev) if chain else None
         sets.append((layers, X, Y, scratch))
 
+    ws_bytes = hinm.hinm_spmm_prepared_workspace(c.M, c.K, c.V, c.Kv, c.dtype, N) if use_prepared else 0
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+
     def step(i):
         layers, X, Y, scratch = sets[i % n_sets]
+        vflag = args.variant << 16
         if chain:
-            ls = [hinm.Layer(c.M, c.K, c.V, c.Kv, c.dtype, v, n, ve, pi, po, hinm.EPI_RELU if l == 0 else 0)
-                  for l, (v, n, ve, pi, po) in enumerate(layers)]
+            ls = [hinm.Layer(c.M, c.K, c.V, c.Kv, c.dtype, v, n, ve, pi, po,
+                             (hinm.EPI_RELU if l == 0 else 0) | (vflag if pr is not None else 0), pr)
+                  for l, (v, n, ve, pi, po, pr) in enumerate(layers)]
             hinm.hinm_chain(ls, N, X, ldn, Y, ldn, scratch, scratch.numel())
         else:
-            v, n, ve, pi, po = layers[0]
-            hinm.hinm_spmm(c.M, c.K, c.V, c.Kv, c.dtype, N, v, n, ve, pi, po, X, ldn, Y, ldn, 0)
+            v, n, ve, pi, po, pr = layers[0]
+            if pr is not None:
+                hinm.hinm_spmm_prepared(c.M, c.K, c.V, c.Kv, c.dtype, N, pr, X, ldn, Y, ldn, vflag, ws, ws_bytes)
+            else:
+                hinm.hinm_spmm(c.M, c.K, c.V, c.Kv, c.dtype, N, v, n, ve, pi, po, X, ldn, Y, ldn, 0)
 
     flops_dense_equiv = 2.0 * c.M * c.K * N * n_layers
     flops_stored = 2.0 * c.M * (c.Kv // 2) * N * n_layers
@@ -205,7 +225,10 @@ def main():
         ach = flops_stored / n_layers / (kernel_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / MFMA_DENSE_PEAK_TFLOPS, 4), "traffic": None}
-    roofline["kernel"] = "spmm_skinny_kernel" if N <= 16 or c.V % 32 else "spmm_tile_kernel"
+    if use_prepared:
+        roofline["kernel"] = "spmm_tile_prepared_kernel"
+    else:
+        roofline["kernel"] = "spmm_skinny_kernel" if N <= 16 or c.V % 32 else "spmm_tile_kernel"
     roofline["kernel_ms_avg"] = round(kernel_ms, 6)
     roofline["kernel_ms_median_event_pair"] = round(kernel_ms_med, 6)
     roofline["algorithmic_bytes_per_launch"] = bytes_step // n_layers
@@ -246,6 +269,9 @@ def main():
                    "Kv": c.Kv, "N": N, "layers": n_layers,
                    "permutation": "identity" if args.identity else "seeded random pi_in/pi_out",
                    "buffer_sets_rotated": n_sets,
+                   "entry_point": ("hinm_chain" if chain else "hinm_spmm")
+                   + ("_prepared" if use_prepared and not chain else "") + (" (prepared layers)" if chain and use_prepared else ""),
+                   "variant": args.variant,
                    "launch": "host loop" if graph is None else "one HIP graph of K steps"},
         "gpu_ms_per_step_events": round(gpu_ms_per_step, 6),
         "hbm_gbps_algorithmic": round(bytes_step / (gpu_ms_per_step * 1e-3) / 1e9, 1),

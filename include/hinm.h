@@ -79,7 +79,10 @@ enum {
   /* kernel choice; default (none set) picks by shape */
   HINM_KERNEL_REFERENCE = 0x100u, /* one thread per output element, plain FMA; any V */
   HINM_KERNEL_SMFMAC = 0x200u,    /* sparse-MFMA tile kernel; needs V in {16,32,64,96,128} */
-  HINM_KERNEL_GEMV = 0x400u       /* wavefront-per-row kernel for very small N (N <= 8) */
+  HINM_KERNEL_GEMV = 0x400u,      /* k-split skinny kernel; N <= 16 */
+  /* hinm_spmm_prepared only, tuning aid: bits 16..19 pin one kernel configuration (0 = by shape) */
+  HINM_VARIANT_SHIFT = 16,
+  HINM_VARIANT_MASK = 0xF0000u
 };
 
 typedef struct {
@@ -118,14 +121,44 @@ hinm_status hinm_spmm(const hinm_shape* shape, int32_t N,
                       const void* X, int64_t ldx, void* Y, int64_t ldy,
                       uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- device-tuned form -----------------------------------------------------------------------
+ * Section 3.2 settles every layer's channel orders offline and rewrites the vector indices
+ * accordingly, so that at run time the kernel follows a single index per input row.
+ * hinm_prepare does that rewriting once per layer, on the GPU: it composes the vector index
+ * with pi_in into a gather table, keeps pi_out, and re-orders the stored values and NM nibbles into
+ * the lane order of the sparse-MFMA operands so that the kernels stream them with full-width
+ * contiguous loads.  The result is an opaque buffer (a pure re-ordering of the canonical arrays
+ * plus the two permutations; parity is judged on the canonical arrays and on the products).
+ * Needs V % 32 == 0 (HINM_ERR_UNSUPPORTED otherwise: use hinm_spmm).  `prepared` is 256-byte
+ * aligned device memory of hinm_prepare_sizes bytes; it must stay unchanged while products that
+ * use it are in flight. */
+hinm_status hinm_prepare_sizes(const hinm_shape* shape, size_t* prepared_bytes);
+hinm_status hinm_prepare(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx,
+                         const int32_t* vec_idx, const int32_t* pi_in, const int32_t* pi_out,
+                         void* prepared, size_t prepared_bytes, void* stream);
+
+/* Same product as hinm_spmm, computed from a prepared layer (its pi_in / pi_out are the ones given
+ * to hinm_prepare).  Flags: HINM_EPI_RELU, HINM_OUT_F32.
+ * Few-column shapes (N <= 32) split each tile's kept columns over several workgroups, which leave
+ * fp32 partial tiles in `workspace`; the workgroup that finishes a tile last adds them up in a
+ * fixed order, so results are reproducible.  hinm_spmm_prepared_workspace gives the bytes needed
+ * (0 for shapes that need none).  The workspace is 256-byte aligned device memory that the CALLER
+ * ZERO-FILLS ONCE before its first use; every call returns it zero-filled where it must be, so it
+ * can be reused by later calls on the same stream, but not by calls that may overlap in time. */
+hinm_status hinm_spmm_prepared_workspace(const hinm_shape* shape, int32_t N, size_t* workspace_bytes);
+hinm_status hinm_spmm_prepared(const hinm_shape* shape, int32_t N, const void* prepared,
+                               const void* X, int64_t ldx, void* Y, int64_t ldy, uint32_t flags,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 typedef struct {
   hinm_shape shape;
-  const void* vals;
+  const void* vals;       /* canonical arrays; may be NULL when `prepared` is given */
   const uint8_t* nm_idx;
   const int32_t* vec_idx;
-  const int32_t* pi_in;   /* NULL = identity */
-  const int32_t* pi_out;  /* NULL = identity */
+  const int32_t* pi_in;   /* NULL = identity (ignored when `prepared` is given) */
+  const int32_t* pi_out;  /* NULL = identity (ignored when `prepared` is given) */
   uint32_t flags;         /* HINM_EPI_RELU and kernel choice; HINM_OUT_F32 only on the last layer */
+  const void* prepared;   /* NULL, or the layer's hinm_prepare buffer (then the fast kernels run) */
 } hinm_layer;
 
 /* Bytes of `scratch` hinm_chain needs for L layers at N columns (the

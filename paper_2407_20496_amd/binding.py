@@ -27,7 +27,7 @@ class _Shape(C.Structure):
 
 class _Layer(C.Structure):
     _fields_ = [("shape", _Shape), ("vals", C.c_void_p), ("nm_idx", C.c_void_p), ("vec_idx", C.c_void_p),
-                ("pi_in", C.c_void_p), ("pi_out", C.c_void_p), ("flags", C.c_uint32)]
+                ("pi_in", C.c_void_p), ("pi_out", C.c_void_p), ("flags", C.c_uint32), ("prepared", C.c_void_p)]
 
 
 def library_path() -> str:
@@ -36,7 +36,8 @@ def library_path() -> str:
 
 def exported_symbols() -> Tuple[str, ...]:
     """Entry points include/hinm.h declares."""
-    return ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain",
+    return ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_prepare_sizes", "hinm_prepare",
+            "hinm_spmm_prepared_workspace", "hinm_spmm_prepared", "hinm_chain_sizes", "hinm_chain",
             "hinm_status_str", "hinm_version")
 
 
@@ -65,7 +66,14 @@ def load_library():
     lib.hinm_chain_sizes.argtypes = [C.c_int32, C.POINTER(_Layer), C.c_int32, szp]
     lib.hinm_chain.argtypes = [C.c_int32, C.POINTER(_Layer), C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
-    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain"):
+    lib.hinm_prepare_sizes.argtypes = [sp, szp]
+    lib.hinm_prepare.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+    lib.hinm_spmm_prepared_workspace.argtypes = [sp, C.c_int32, szp]
+    lib.hinm_spmm_prepared.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                       C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
+    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain",
+                 "hinm_prepare_sizes", "hinm_prepare", "hinm_spmm_prepared_workspace", "hinm_spmm_prepared"):
         getattr(lib, name).restype = C.c_int
     lib.hinm_status_str.argtypes = [C.c_int]
     lib.hinm_status_str.restype = C.c_char_p
@@ -156,6 +164,37 @@ def hinm_spmm(M, K, V, Kv, dtype, N, vals, nm_idx, vec_idx, pi_in, pi_out, X, ld
                          _ptr(workspace), int(workspace_bytes), _stream(stream)), "hinm_spmm")
 
 
+def hinm_prepare_sizes(M, K, V, Kv, dtype) -> int:
+    lib = load_library()
+    out = C.c_size_t(0)
+    _check(lib.hinm_prepare_sizes(C.byref(_shape(M, K, V, Kv, dtype)), C.byref(out)), "hinm_prepare_sizes")
+    return int(out.value)
+
+
+def hinm_prepare(M, K, V, Kv, dtype, vals, nm_idx, vec_idx, pi_in, pi_out, prepared, prepared_bytes,
+                 stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_prepare(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(vals), _ptr(nm_idx), _ptr(vec_idx),
+                            _ptr(pi_in), _ptr(pi_out), _ptr(prepared), int(prepared_bytes), _stream(stream)),
+           "hinm_prepare")
+
+
+def hinm_spmm_prepared_workspace(M, K, V, Kv, dtype, N) -> int:
+    lib = load_library()
+    out = C.c_size_t(0)
+    _check(lib.hinm_spmm_prepared_workspace(C.byref(_shape(M, K, V, Kv, dtype)), int(N), C.byref(out)),
+           "hinm_spmm_prepared_workspace")
+    return int(out.value)
+
+
+def hinm_spmm_prepared(M, K, V, Kv, dtype, N, prepared, X, ldx, Y, ldy, flags=0, workspace=None,
+                       workspace_bytes=0, stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_spmm_prepared(C.byref(_shape(M, K, V, Kv, dtype)), int(N), _ptr(prepared), _ptr(X), int(ldx),
+                                  _ptr(Y), int(ldy), int(flags), _ptr(workspace), int(workspace_bytes),
+                                  _stream(stream)), "hinm_spmm_prepared")
+
+
 @dataclass
 class Layer:
     M: int
@@ -169,13 +208,14 @@ class Layer:
     pi_in: object = None
     pi_out: object = None
     flags: int = 0
+    prepared: object = None
 
 
 def _layers(layers: Sequence[Layer]):
     arr = (_Layer * len(layers))()
     for i, l in enumerate(layers):
         arr[i] = _Layer(_shape(l.M, l.K, l.V, l.Kv, l.dtype), _ptr(l.vals), _ptr(l.nm_idx), _ptr(l.vec_idx),
-                        _ptr(l.pi_in), _ptr(l.pi_out), int(l.flags))
+                        _ptr(l.pi_in), _ptr(l.pi_out), int(l.flags), _ptr(l.prepared))
     return arr
 
 

@@ -1,6 +1,8 @@
 // C-ABI entry points of libhinm: host-side argument validation and kernel dispatch.
 // Every check here runs before anything is launched, so the error paths need no GPU.
 #include "hinm_internal.h"
+#include "prepared_layout.h"
+
 
 namespace {
 
@@ -108,6 +110,12 @@ hinm_status hinm_spmm(const hinm_shape* shape, int32_t N, const void* vals, cons
   return run_spmm(a, flags, static_cast<hipStream_t>(stream));
 }
 
+static hinm_status check_prepared_call(const hinm_shape* shape, int32_t N, const void* prepared, const void* X,
+                                       int64_t ldx, const void* Y, int64_t ldy, uint32_t flags);
+static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
+                                void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes,
+                                hipStream_t stream);
+
 static hinm_status check_chain(int32_t L, const hinm_layer* layers, int32_t N, size_t* bytes_per_buffer) {
   if (!layers) return HINM_ERR_NULL;
   if (L <= 0 || N <= 0) return HINM_ERR_SHAPE;
@@ -115,7 +123,7 @@ static hinm_status check_chain(int32_t L, const hinm_layer* layers, int32_t N, s
   for (int l = 0; l < L; ++l) {
     hinm_status st = check_shape(&layers[l].shape);
     if (st != HINM_OK) return st;
-    if (!layers[l].vals || !layers[l].nm_idx || !layers[l].vec_idx) return HINM_ERR_NULL;
+    if (!layers[l].prepared && (!layers[l].vals || !layers[l].nm_idx || !layers[l].vec_idx)) return HINM_ERR_NULL;
     if (layers[l].shape.dtype != layers[0].shape.dtype) return HINM_ERR_DTYPE;
     if (l > 0 && layers[l].shape.K != layers[l - 1].shape.M) return HINM_ERR_SHAPE;
     if (l + 1 < L && (layers[l].flags & HINM_OUT_F32)) return HINM_ERR_UNSUPPORTED;
@@ -150,8 +158,12 @@ hinm_status hinm_chain(int32_t L, const hinm_layer* layers, int32_t N, const voi
   for (int l = 0; l < L; ++l) {
     const void* in = (l == 0) ? X : scratch;
     void* out = (l == L - 1) ? Y : scratch;
-    st = check_spmm(&layers[l].shape, N, layers[l].vals, layers[l].nm_idx, layers[l].vec_idx, in,
-                    l == 0 ? ldx : ldh, out, l == L - 1 ? ldy : ldh, layers[l].flags);
+    if (layers[l].prepared)
+      st = check_prepared_call(&layers[l].shape, N, layers[l].prepared, in, l == 0 ? ldx : ldh, out,
+                               l == L - 1 ? ldy : ldh, layers[l].flags);
+    else
+      st = check_spmm(&layers[l].shape, N, layers[l].vals, layers[l].nm_idx, layers[l].vec_idx, in,
+                      l == 0 ? ldx : ldh, out, l == L - 1 ? ldy : ldh, layers[l].flags);
     if (st != HINM_OK) return st;
   }
   char* buf[2] = {static_cast<char*>(scratch), static_cast<char*>(scratch) + per};
@@ -162,14 +174,83 @@ hinm_status hinm_chain(int32_t L, const hinm_layer* layers, int32_t N, const voi
     void* out = last ? Y : static_cast<void*>(buf[l & 1]);
     const int64_t ld_out = last ? ldy : ldh;
     const hinm_layer& ly = layers[l];
-    SpmmArgs a{ly.shape, N, ly.vals, ly.nm_idx, ly.vec_idx, ly.pi_in, ly.pi_out, in, ld_in, out, ld_out,
-               (ly.flags & HINM_EPI_RELU) != 0, (ly.flags & HINM_OUT_F32) != 0};
-    st = run_spmm(a, ly.flags, static_cast<hipStream_t>(stream));
+    if (ly.prepared) {
+      st = run_prepared(&ly.shape, N, ly.prepared, in, ld_in, out, ld_out, ly.flags, nullptr, 0,
+                        static_cast<hipStream_t>(stream));
+    } else {
+      SpmmArgs a{ly.shape, N, ly.vals, ly.nm_idx, ly.vec_idx, ly.pi_in, ly.pi_out, in, ld_in, out, ld_out,
+                 (ly.flags & HINM_EPI_RELU) != 0, (ly.flags & HINM_OUT_F32) != 0};
+      st = run_spmm(a, ly.flags, static_cast<hipStream_t>(stream));
+    }
     if (st != HINM_OK) return st;
     in = out;
     ld_in = ld_out;
   }
   return HINM_OK;
+}
+
+
+hinm_status hinm_prepare_sizes(const hinm_shape* shape, size_t* prepared_bytes) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (!prepared_bytes) return HINM_ERR_NULL;
+  if (shape->V % 32 != 0 || shape->V > 128) return HINM_ERR_UNSUPPORTED;
+  *prepared_bytes = prepared_layout(*shape).total_bytes;
+  return HINM_OK;
+}
+
+hinm_status hinm_prepare(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
+                         const int32_t* pi_in, const int32_t* pi_out, void* prepared, size_t prepared_bytes,
+                         void* stream) {
+  size_t need = 0;
+  hinm_status st = hinm_prepare_sizes(shape, &need);
+  if (st != HINM_OK) return st;
+  if (!vals || !nm_idx || !vec_idx || !prepared) return HINM_ERR_NULL;
+  if (prepared_bytes < need || !aligned(prepared, 256)) return HINM_ERR_WORKSPACE;
+  hipError_t e = launch_prepare(*shape, vals, nm_idx, vec_idx, pi_in, pi_out, prepared,
+                                static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
+hinm_status hinm_spmm_prepared_workspace(const hinm_shape* shape, int32_t N, size_t* workspace_bytes) {
+  size_t need = 0;
+  hinm_status st = hinm_prepare_sizes(shape, &need);
+  if (st != HINM_OK) return st;
+  if (!workspace_bytes) return HINM_ERR_NULL;
+  if (N <= 0) return HINM_ERR_SHAPE;
+  *workspace_bytes = 0;
+  return HINM_OK;
+}
+
+static hinm_status check_prepared_call(const hinm_shape* shape, int32_t N, const void* prepared, const void* X,
+                                       int64_t ldx, const void* Y, int64_t ldy, uint32_t flags) {
+  size_t need = 0;
+  hinm_status st = hinm_prepare_sizes(shape, &need);
+  if (st != HINM_OK) return st;
+  if (!prepared || !X || !Y) return HINM_ERR_NULL;
+  if (N <= 0 || ldx < N || ldy < N) return HINM_ERR_SHAPE;
+  if (ldx % 8 != 0 || ldy % 8 != 0) return HINM_ERR_SHAPE;
+  if (!aligned(prepared, 256) || !aligned(X, 16) || !aligned(Y, 16)) return HINM_ERR_SHAPE;
+  if (flags & ~(uint32_t)(HINM_EPI_RELU | HINM_OUT_F32 | HINM_VARIANT_MASK)) return HINM_ERR_UNSUPPORTED;
+  return HINM_OK;
+}
+
+static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
+                                void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes,
+                                hipStream_t stream) {
+  PreparedArgs a{*shape, N, prepared, X, ldx, Y, ldy, (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0,
+                 (int)((flags & HINM_VARIANT_MASK) >> HINM_VARIANT_SHIFT), workspace, workspace_bytes};
+  hipError_t e = launch_spmm_tile_prepared(a, stream);
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
+hinm_status hinm_spmm_prepared(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
+                               void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  hinm_status st = check_prepared_call(shape, N, prepared, X, ldx, Y, ldy, flags);
+  if (st != HINM_OK) return st;
+  return run_prepared(shape, N, prepared, X, ldx, Y, ldy, flags, workspace, workspace_bytes,
+                      static_cast<hipStream_t>(stream));
 }
 
 const char* hinm_status_str(hinm_status s) {

@@ -63,4 +63,26 @@ hipError_t launch_spmm_tile(const SpmmArgs& a, hipStream_t stream);
 bool spmm_skinny_supported(const SpmmArgs& a);
 hipError_t launch_spmm_skinny(const SpmmArgs& a, hipStream_t stream);
 
+
+// ---- device-tuned ("prepared") layer form -------------------------------------------------------------
+hipError_t launch_prepare(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
+                          const int32_t* pi_in, const int32_t* pi_out, void* prepared, hipStream_t stream);
+
+struct PreparedArgs {
+  hinm_shape s;
+  int32_t N;
+  const void* prepared;
+  const void* X;
+  int64_t ldx;
+  void* Y;
+  int64_t ldy;
+  bool relu;
+  bool out_f32;
+  int tile_variant;  // 0 = choose by shape; 1.. = a fixed (column block, stage size, depth) choice
+  void* workspace;
+  size_t workspace_bytes;
+};
+
+hipError_t launch_spmm_tile_prepared(const PreparedArgs& a, hipStream_t stream);
+
 }  // namespace hinm

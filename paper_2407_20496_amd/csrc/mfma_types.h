@@ -71,4 +71,28 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const void* lds_ptr) {
   return __builtin_bit_cast(u32x2, v);
 }
 
+
+// Four transposing LDS reads from one per-lane base address plus compile-time byte offsets, issued as
+// raw instructions: the compiler would otherwise hold every such read until all direct-to-LDS
+// copies in flight have landed, which serialises the copy pipeline.  The caller must execute
+// lds_wait_tr() on the results before using them.
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void lds_read_tr16_x4(uint32_t lds_addr, u32x2& r0, u32x2& r1, u32x2& r2, u32x2& r3) {
+  static_assert(O0 >= 0 && O3 < 65536 && O1 < 65536 && O2 < 65536, "DS offset field is 16 bits");
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %4 offset:%5\n\t"
+      "ds_read_b64_tr_b16 %1, %4 offset:%6\n\t"
+      "ds_read_b64_tr_b16 %2, %4 offset:%7\n\t"
+      "ds_read_b64_tr_b16 %3, %4 offset:%8"
+      : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
+      : "v"(lds_addr), "n"(O0), "n"(O1), "n"(O2), "n"(O3));
+}
+
+// Waits for every LDS operation of this wave and ties the wait to the given registers, so that no
+// use of them can be scheduled before it.
+__device__ __forceinline__ void lds_wait_tr(u32x8& b0, u32x8& b1) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b0), "+v"(b1));
+}
+__device__ __forceinline__ void lds_wait_tr(u32x8& b0) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b0)); }
+
 }  // namespace hinm

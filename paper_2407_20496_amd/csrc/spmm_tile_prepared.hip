@@ -1,0 +1,385 @@
+// HiNM sparse GEMM with fused channel permutation, many columns, from the device-tuned layer form
+// (arXiv 2407.20496, Section 3.2 and Section 5.3; layout in prepared_layout.h).
+//
+// One workgroup computes one tile of V = 32 * RB output channels for a block of NB columns.  The
+// tile's kept input channels are walked in stages of KS = 32 * KSUB columns, ST stages deep:
+//   global -> LDS : direct-to-LDS loads, no registers in between.  The KS input rows named by the
+//                   gather table (vector index composed with the input-channel order) arrive as
+//                   contiguous NB-column row segments; the tile's stored values and NM nibbles for
+//                   the stage are one contiguous chunk already in MFMA lane order.  Channel
+//                   re-ordering costs nothing here: the table lookup is the one the format needs.
+//   LDS -> MFMA   : every wave owns 64 of the NB columns and all V rows; A fragments are linear
+//                   16-byte LDS reads, B fragments use the transposing LDS read on rows whose
+//                   32-byte units are XOR-swizzled (applied on the source address of the copy) so
+//                   that the four rows of one read fall on different banks; the NM nibbles go
+//                   unchanged into the index operand of the 32x32x32 sparse MFMA.
+//   epilogue      : fp32 accumulators -> optional ReLU -> 16 bit, staged through LDS so that every
+//                   output row leaves as one contiguous segment to row pi_out[r] of Y.
+// The stage being multiplied, and the ST - 1 stages in flight behind it, are separated by one
+// workgroup barrier per stage and by explicit counts of outstanding copies.
+#include "hinm_internal.h"
+#include "mfma_types.h"
+#include "prepared_layout.h"
+
+#include <type_traits>
+
+namespace hinm {
+namespace {
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+
+__device__ __forceinline__ void copy16_to_lds(const void* src_lane, void* lds_wave_base) {
+  // every lane copies 16 bytes; lane l lands at lds_wave_base + 16 l
+  __builtin_amdgcn_global_load_lds((global_void_t*)src_lane, (lds_void_t*)lds_wave_base, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(n) with everything else left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4, lgkmcnt 11:8)
+template <int N>
+__device__ __forceinline__ void wait_copies_outstanding() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+// Outstanding copies allowed = `later` stages of (B + extra) copies each; extra is 0..3, later 0..2.
+template <int B>
+__device__ __forceinline__ void wait_copies_outstanding(int later, int extra) {
+  if (later == 0) {
+    wait_copies_outstanding<0>();
+  } else if (later == 1) {
+    switch (extra) {
+      case 0: wait_copies_outstanding<B>(); break;
+      case 1: wait_copies_outstanding<B + 1>(); break;
+      case 2: wait_copies_outstanding<B + 2>(); break;
+      default: wait_copies_outstanding<B + 3>(); break;
+    }
+  } else {
+    switch (extra) {
+      case 0: wait_copies_outstanding<2 * B>(); break;
+      case 1: wait_copies_outstanding<2 * B + 2>(); break;
+      case 2: wait_copies_outstanding<2 * B + 4>(); break;
+      default: wait_copies_outstanding<2 * B + 6>(); break;
+    }
+  }
+}
+
+// 32-byte units of a row are stored at unit ^ swizzle(row & 3): the four rows a transposing read
+// touches then sit on four different bank groups, for 16-lane as well as 32-lane LDS passes.
+__host__ __device__ constexpr int swizzle_of_row(int r) { return ((r & 3) << 1) | (((r >> 1) ^ r) & 1); }
+
+template <int RB, int NB, int KSUB, int ST>
+struct TileCfg {
+  static constexpr int NW = NB / 64;
+  static constexpr int THREADS = NW * 64;
+  static constexpr int KS = 32 * KSUB;
+  static constexpr int ROW_BYTES = NB * 2;
+  static constexpr int B_BYTES = KS * ROW_BYTES;
+  static constexpr int A_RB_BYTES = KSUB * 1024 + 256;          // per row block: values of KSUB substeps + nibbles
+  static constexpr int A_GRANULES = RB * (KSUB * 64 + 16);
+  static constexpr int A_INSTR = (A_GRANULES + 63) / 64;         // wave-wide copies for A per stage
+  static constexpr int A_BYTES = A_INSTR * 1024;                 // rounded up: the last copy may overshoot
+  static constexpr int STAGE_BYTES = B_BYTES + A_BYTES;
+  static constexpr int B_PER_WAVE = (NB == 512 ? KS : KS / 2) / NW;  // wave-wide copies for B per wave and stage
+  static constexpr int ROWS_PER_WAVE = KS / NW;
+  static constexpr int Y_STRIDE = NB * 2 + 16;
+  static constexpr int EPI_BYTES = 32 * RB * Y_STRIDE;
+  static constexpr int LDS_BYTES = (ST * STAGE_BYTES > EPI_BYTES) ? ST * STAGE_BYTES : EPI_BYTES;
+  static_assert(NB == 256 || NB == 512, "column block");
+  static_assert(B_PER_WAVE == 4 * KSUB, "copy split");
+  static_assert(ST >= 2 && ST <= 4 && (A_INSTR + NW - 1) / NW <= 3, "wait table covers these");
+};
+
+template <int DT, int RB, int NB, int KSUB, int ST>
+__global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
+    const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
+    const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
+    int T, int S64, int N, int n_blocks, int work_per_xcd, bool relu, bool out_f32) {
+  using C = TileCfg<RB, NB, KSUB, ST>;
+  constexpr int V = 32 * RB;
+  constexpr int NW = C::NW;
+  constexpr int KS = C::KS;
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+  // Consecutive workgroup ids go to different XCDs: give every XCD a contiguous run of the
+  // column-block-major work list, so the tiles running together on one XCD share a column panel of
+  // X in that XCD's L2.
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int work = xcd * work_per_xcd + slot;
+  if (slot >= work_per_xcd || work >= n_blocks * T) return;
+  const int nb = work / T;
+  const int t = work % T;
+  const int n0 = nb * NB;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int stages_total = S64 * (2 / KSUB);  // stages of KS columns
+  const int Kp = S64 * 64;
+
+  const int32_t* gt = gather + (size_t)t * Kp;
+  const uint8_t* a_tile = prep_blocks + (size_t)t * S64 * RB * kPrepBlockBytes;
+
+  // ---- copy roles ---------------------------------------------------------------------------------
+  // B: this wave copies rows [wave * ROWS_PER_WAVE, +ROWS_PER_WAVE) of every stage.
+  //    NB = 512: one copy per row, lane = 16-byte granule position in the row;
+  //    NB = 256: one copy per row pair, lanes 0..31 the even row, 32..63 the odd row.
+  // A copy's source is a wave-uniform row base (X row from the gather table, or the zero row for
+  // padded kept columns) plus a per-lane byte offset that depends only on row % 4 (the swizzle):
+  // the offsets are computed once.  Lanes whose columns lie beyond N re-read the block's first
+  // columns instead: those accumulator columns are never stored.
+  const int gpos = (NB == 512) ? lane : (lane & 31);
+  const int half = (NB == 512) ? 0 : (lane >> 5);
+  uint32_t b_src_off[4];
+#pragma unroll
+  for (int r4 = 0; r4 < 4; ++r4) {
+    const int granule = (((gpos >> 1) ^ swizzle_of_row(r4)) << 1) | (gpos & 1);  // which 16 bytes of the row segment
+    b_src_off[r4] = (n0 + granule * 8 < N) ? granule * 16 : 0;
+  }
+  // NB = 256: lane in half h copies row 2 k + h, so row % 4 is h for even k and 2 + h for odd k
+  const uint32_t b_off_even_k = half ? b_src_off[1] : b_src_off[0];
+  const uint32_t b_off_odd_k = half ? b_src_off[3] : b_src_off[2];
+  // A: wave-wide copies number wave, wave + NW, ... of the stage's chunk; per-lane source offsets
+  constexpr int A_ROUNDS = (C::A_INSTR + NW - 1) / NW;
+  uint32_t a_src_off[A_ROUNDS];
+  uint32_t a_src_odd_stage[A_ROUNDS];  // KSUB == 1: extra offset on odd stages (second half of the values)
+#pragma unroll
+  for (int m = 0; m < A_ROUNDS; ++m) {
+    const int gran = min((wave + m * NW) * 64 + lane, C::A_GRANULES - 1);  // overshoot re-reads the last granule
+    if constexpr (KSUB == 2) {
+      a_src_off[m] = gran * 16;
+      a_src_odd_stage[m] = 0;
+    } else {
+      const int rb = gran / 80, r = gran % 80;
+      a_src_off[m] = rb * kPrepBlockBytes + ((r < 64) ? r * 16 : kPrepIdxOffset + (r - 64) * 16);
+      a_src_odd_stage[m] = (r < 64) ? 1024 : 0;
+    }
+  }
+  typedef int rows_t __attribute__((ext_vector_type(C::ROWS_PER_WAVE)));
+  auto load_rows = [&](int stage_idx) -> rows_t {
+    // the wave's ROWS_PER_WAVE consecutive gather-table entries of a stage (wave-uniform: scalar load)
+    const int st = min(stage_idx, stages_total - 1);
+    return *reinterpret_cast<const rows_t*>(gt + st * KS + wave * C::ROWS_PER_WAVE);
+  };
+  const uint8_t* x_block = reinterpret_cast<const uint8_t*>(X + n0);
+  auto row_base = [&](int g) -> const uint8_t* {  // wave-uniform
+    return (g >= 0) ? x_block + (size_t)g * ldx * 2 : zeros;
+  };
+  auto issue_stage = [&](int stage_idx, uint8_t* stage, const rows_t rows) {
+#pragma unroll
+    for (int k = 0; k < C::B_PER_WAVE; ++k) {
+      if constexpr (NB == 512) {
+        copy16_to_lds(row_base(rows[k]) + b_src_off[k & 3], stage + (wave * C::ROWS_PER_WAVE + k) * C::ROW_BYTES);
+      } else {
+        const uint8_t* be = row_base(rows[2 * k]);
+        const uint8_t* bo = row_base(rows[2 * k + 1]);
+        const uint8_t* src = (half ? bo : be) + ((k & 1) ? b_off_odd_k : b_off_even_k);
+        copy16_to_lds(src, stage + (wave * C::ROWS_PER_WAVE + 2 * k) * C::ROW_BYTES);
+      }
+    }
+    uint8_t* a_lds = stage + C::B_BYTES;
+    const uint8_t* a_stage = (KSUB == 2) ? a_tile + (size_t)stage_idx * RB * kPrepBlockBytes
+                                         : a_tile + (size_t)(stage_idx >> 1) * RB * kPrepBlockBytes;
+#pragma unroll
+    for (int m = 0; m < A_ROUNDS; ++m) {
+      const int instr = wave + m * NW;
+      if (instr < C::A_INSTR) {  // wave-uniform
+        const uint32_t off = a_src_off[m] + ((stage_idx & 1) ? a_src_odd_stage[m] : 0u);
+        copy16_to_lds(a_stage + off, a_lds + instr * 1024);
+      }
+    }
+  };
+  const int extra_copies = (C::A_INSTR - wave + NW - 1) / NW;  // A copies of this wave per stage
+
+  // ---- MFMA roles -----------------------------------------------------------------------------------
+  const int i32 = lane & 31;  // A row / B column inside a 32-block
+  const int qh = lane >> 5;   // lane group
+  const int i16 = lane & 15;
+  const int sw_lane = swizzle_of_row(i16 >> 2);
+  int b_col_off[2];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) b_col_off[cb] = (((wave * 4 + cb * 2 + (i32 >> 4)) ^ sw_lane) * 32) + (i16 & 3) * 8;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_t*)lds;
+  // per-lane part of the transposing-read address: row 8 qb + (i16 / 4), swizzled column unit
+  uint32_t b_lane_off[2];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) b_lane_off[cb] = (8 * qh + (i16 >> 2)) * C::ROW_BYTES + b_col_off[cb];
+
+  f32x16 acc[RB][2];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[rb][cb][e] = 0.f;
+
+  // B slots 8 h + 4 u .. + 3 of lane group qb <- rows 16 h + 8 qb + 4 u + (0..3) of the substep
+  auto read_b = [&](uint32_t stage_addr, int cb, auto sub_tag) -> u32x8 {
+    constexpr int SUB = decltype(sub_tag)::value;
+    constexpr int R0 = (SUB * 32 + 0) * C::ROW_BYTES, R1 = (SUB * 32 + 4) * C::ROW_BYTES,
+                  R2 = (SUB * 32 + 16) * C::ROW_BYTES, R3 = (SUB * 32 + 20) * C::ROW_BYTES;
+    u32x2 r0, r1, r2, r3;
+    lds_read_tr16_x4<R0, R1, R2, R3>(stage_addr + b_lane_off[cb], r0, r1, r2, r3);
+    return u32x8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
+  };
+
+  auto compute_sub = [&](int stage_idx, const uint8_t* stage, auto sub_tag) {
+    constexpr int SUB = decltype(sub_tag)::value;
+    const uint8_t* as = stage + C::B_BYTES;
+    const uint32_t stage_addr = lds_base + (uint32_t)(stage - lds);
+    u32x8 b0 = read_b(stage_addr, 0, sub_tag);
+    u32x8 b1 = read_b(stage_addr, 1, sub_tag);
+    u32x4 a[RB];
+    int idx[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const uint8_t* blk = as + rb * C::A_RB_BYTES;
+      a[rb] = *reinterpret_cast<const u32x4*>(blk + SUB * 1024 + lane * 16);
+      idx[rb] = *reinterpret_cast<const int*>(blk + KSUB * 1024 + lane * 4);
+      // the index register holds the nibbles of both substeps of a 64-column step
+      if (KSUB == 1 && (stage_idx & 1)) idx[rb] = (int)((uint32_t)idx[rb] >> 16);
+    }
+    lds_wait_tr(b0, b1);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      if constexpr (KSUB == 2 && SUB == 1) {
+        acc[rb][0] = smfmac_32x32x32<DT, 1>(a[rb], b0, acc[rb][0], idx[rb]);
+        acc[rb][1] = smfmac_32x32x32<DT, 1>(a[rb], b1, acc[rb][1], idx[rb]);
+      } else {
+        acc[rb][0] = smfmac_32x32x32<DT, 0>(a[rb], b0, acc[rb][0], idx[rb]);
+        acc[rb][1] = smfmac_32x32x32<DT, 0>(a[rb], b1, acc[rb][1], idx[rb]);
+      }
+    }
+  };
+  auto compute_stage = [&](int stage_idx, const uint8_t* stage) {
+    compute_sub(stage_idx, stage, std::integral_constant<int, 0>{});
+    if constexpr (KSUB == 2) compute_sub(stage_idx, stage, std::integral_constant<int, 1>{});
+  };
+
+  // ---- pipeline ---------------------------------------------------------------------------------------
+#pragma unroll
+  for (int p = 0; p < ST - 1; ++p)
+    if (p < stages_total) issue_stage(p, lds + p * C::STAGE_BYTES, load_rows(p));
+  rows_t rows_next = load_rows(ST - 1);
+  for (int s = 0; s < stages_total; ++s) {
+    // stage s must have landed; the stages issued after it may still be in flight
+    const int later = min(ST - 2, stages_total - 1 - s);
+    if constexpr (ST == 2) wait_copies_outstanding<0>();
+    else wait_copies_outstanding<C::B_PER_WAVE>(later, extra_copies);
+    __builtin_amdgcn_s_barrier();
+    const int nxt = s + ST - 1;
+    if (nxt < stages_total) issue_stage(nxt, lds + (nxt % ST) * C::STAGE_BYTES, rows_next);
+    rows_next = load_rows(nxt + 1);
+    compute_stage(s, lds + (s % ST) * C::STAGE_BYTES);
+  }
+
+  // ---- epilogue -------------------------------------------------------------------------------------
+  // D layout: lane holds column lane % 32, rows 8 * (reg / 4) + 4 * (lane / 32) + reg % 4.
+  if (out_f32) {
+    float* Yf = static_cast<float*>(Y);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = t * V + 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
+        const int64_t out_row = out_rows[r];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          const int n = n0 + wave * 64 + cb * 32 + i32;
+          float v = acc[rb][cb][e];
+          if (relu) v = v > 0.f ? v : 0.f;
+          if (n < N) Yf[out_row * ldy + n] = v;
+        }
+      }
+    return;
+  }
+  __builtin_amdgcn_s_barrier();  // every wave is done reading the stages
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
+        const int col = wave * 64 + cb * 32 + i32;
+        float v = acc[rb][cb][e];
+        if (relu) v = v > 0.f ? v : 0.f;
+        *reinterpret_cast<uint16_t*>(lds + row * C::Y_STRIDE + col * 2) = float_to_bits<DT>(v);
+      }
+  __syncthreads();
+  uint16_t* Yh = static_cast<uint16_t*>(Y);
+  constexpr int LANES_PER_ROW = NB / 8;
+  const int chunk = tid % LANES_PER_ROW;
+  for (int row = tid / LANES_PER_ROW; row < V; row += C::THREADS / LANES_PER_ROW) {
+    const int64_t out_row = out_rows[t * V + row];
+    const int n = n0 + chunk * 8;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * C::Y_STRIDE + chunk * 16);
+    uint16_t* dst = Yh + out_row * ldy + n;
+    if (n + 8 <= N) {
+      *reinterpret_cast<u32x4*>(dst) = v;
+    } else if (n < N) {
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      for (int e = 0; e < N - n; ++e) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+    }
+  }
+}
+
+template <int DT, int RB, int NB, int KSUB, int ST>
+hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream) {
+  using C = TileCfg<RB, NB, KSUB, ST>;
+  const PreparedLayout L = prepared_layout(a.s);
+  const int n_blocks = (a.N + NB - 1) / NB;
+  const int64_t work = (int64_t)n_blocks * L.T;
+  const int work_per_xcd = (int)((work + 7) / 8);
+  auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST>;
+  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
+  kernel<<<dim3((unsigned)(work_per_xcd * 8)), C::THREADS, C::LDS_BYTES, stream>>>(
+      base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),
+      reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset,
+      static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy, L.T, L.S, a.N, n_blocks, work_per_xcd, a.relu, a.out_f32);
+  return hipGetLastError();
+}
+
+template <int DT, int RB>
+hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
+  switch (a.tile_variant) {
+    case 1: return launch_cfg<DT, RB, 256, 2, 2>(a, stream);
+    case 2: return launch_cfg<DT, RB, 256, 2, 3>(a, stream);
+    case 3: return launch_cfg<DT, RB, 512, 2, 2>(a, stream);
+    case 4: return launch_cfg<DT, RB, 256, 1, 3>(a, stream);
+    case 5: return launch_cfg<DT, RB, 256, 1, 4>(a, stream);
+    case 6: return launch_cfg<DT, RB, 512, 1, 3>(a, stream);
+    case 7: return launch_cfg<DT, RB, 512, 1, 4>(a, stream);
+    default: break;
+  }
+  return launch_cfg<DT, RB, 256, 2, 3>(a, stream);
+}
+
+}  // namespace
+
+hipError_t launch_spmm_tile_prepared(const PreparedArgs& a, hipStream_t stream) {
+  const int RB = a.s.V / 32;
+#define HINM_RB(DT)                                   \
+  switch (RB) {                                       \
+    case 1: return launch_rb<DT, 1>(a, stream);       \
+    case 2: return launch_rb<DT, 2>(a, stream);       \
+    case 3: return launch_rb<DT, 3>(a, stream);       \
+    case 4: return launch_rb<DT, 4>(a, stream);       \
+  }
+  if (a.s.dtype == HINM_F16) {
+    HINM_RB(HINM_F16)
+  } else {
+    HINM_RB(HINM_BF16)
+  }
+#undef HINM_RB
+  return hipErrorInvalidValue;
+}
+
+}  // namespace hinm

@@ -95,3 +95,46 @@ def check_close(got_f64: np.ndarray, want_f64: np.ndarray, rel_fro=1e-3, max_abs
     mx = np.abs(diff).max() if diff.size else 0.0
     assert fro <= rel_fro and mx <= max_abs, f"{what}: rel-Fro {fro:.3e} (<= {rel_fro}), max-abs {mx:.3e} (<= {max_abs})"
     return fro, mx
+
+
+class Prepared:
+    def __init__(self, p: Packed, buf, nbytes, pi_in, pi_out):
+        self.p, self.buf, self.nbytes, self.pi_in, self.pi_out = p, buf, nbytes, pi_in, pi_out
+
+
+def gpu_prepare(p: Packed, pi_in, pi_out) -> Prepared:
+    nbytes = hinm.hinm_prepare_sizes(p.M, p.K, p.V, p.Kv, p.dtype)
+    buf = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=DEV)
+    hinm.hinm_prepare(p.M, p.K, p.V, p.Kv, p.dtype, p.vals, p.nm_idx, p.vec_idx,
+                      None if pi_in is None else dev_i32(pi_in), None if pi_out is None else dev_i32(pi_out),
+                      buf, nbytes)
+    torch.cuda.synchronize()
+    return Prepared(p, buf, nbytes, pi_in, pi_out)
+
+
+def gpu_spmm_prepared(pr: Prepared, X_bits: np.ndarray, flags=0, variant=0, ldx=None, ldy=None, X_dev=None):
+    p = pr.p
+    K, N = X_bits.shape
+    ldx = ldx or (N + 7) // 8 * 8
+    ldy = ldy or (N + 7) // 8 * 8
+    if X_dev is None:
+        Xp = np.zeros((K, ldx), dtype=np.uint16)
+        Xp[:, :N] = X_bits
+        X_dev = dev_bits(Xp)
+    f32 = bool(flags & hinm.OUT_F32)
+    Y = (torch.full((p.M, ldy), float("nan"), dtype=torch.float32, device=DEV) if f32
+         else torch.full((p.M, ldy), 0x7B7B, dtype=torch.int16, device=DEV))
+    wsb = hinm.hinm_spmm_prepared_workspace(p.M, p.K, p.V, p.Kv, p.dtype, N)
+    ws = torch.zeros(max(wsb, 1), dtype=torch.uint8, device=DEV)
+    hinm.hinm_spmm_prepared(p.M, p.K, p.V, p.Kv, p.dtype, N, pr.buf, X_dev, ldx, Y, ldy, flags | (variant << 16),
+                            ws if wsb else None, wsb)
+    torch.cuda.synchronize()
+    if wsb:
+        pr.last_workspace = ws
+    if f32:
+        out = Y.cpu().numpy()
+        assert np.all(np.isnan(out[:, N:])), "columns beyond N were written"
+        return out[:, :N].copy()
+    out = host_bits(Y)
+    assert np.all(out[:, N:] == 0x7B7B), "columns beyond N were written"
+    return out[:, :N].copy()

@@ -1,0 +1,125 @@
+"""GPU parity of the device-tuned path (hinm_prepare + hinm_spmm_prepared) against the CPU oracle,
+and of the prepared buffer against the canonical arrays it re-orders."""
+import numpy as np
+import pytest
+
+import hinm_synth as synth
+from oracle import hinm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+OUT_F32, RELU = 2, 1
+VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7]
+
+
+def _ulp_bf16(y):
+    e = np.floor(np.log2(np.maximum(np.abs(y), 2.0 ** -14)))
+    return np.exp2(e - 7)
+
+
+def _unswizzle(buf: np.ndarray, M, K, V, Kv):
+    """Decode the prepared buffer (layout documented in csrc/prepared_layout.h) back into the
+    canonical arrays plus the gather table and output rows."""
+    T, RB = M // V, V // 32
+    Kp = (Kv + 63) // 64 * 64
+    S = Kp // 64
+    al = lambda x: (x + 255) // 256 * 256
+    a_bytes = T * S * RB * 2304
+    g_off = al(a_bytes)
+    o_off = g_off + al(T * Kp * 4)
+    z_off = o_off + al(M * 4)
+    blocks = buf[:a_bytes].reshape(T, S, RB, 2304)
+    vals_u16 = blocks[..., :2048].copy().view(np.uint16).reshape(T, S, RB, 2, 64, 8)
+    idx_u32 = blocks[..., 2048:].copy().view(np.uint32).reshape(T, S, RB, 64)
+    G = Kp // 4
+    vals = np.zeros((M, G * 2), dtype=np.uint16)
+    nib = np.zeros((M, G), dtype=np.uint8)
+    for lane in range(64):
+        i, qa = lane % 32, lane // 32
+        for sub in range(2):
+            for k in range(4):
+                # group 16 s + 8 sub + 4 qa + k of row 32 rb + i
+                for s in range(S):
+                    g = 16 * s + 8 * sub + 4 * qa + k
+                    rows = (np.arange(T)[:, None] * V + 32 * np.arange(RB)[None, :] + i).reshape(-1)
+                    vals[rows, 2 * g] = vals_u16[:, s, :, sub, lane, 2 * k].reshape(-1)
+                    vals[rows, 2 * g + 1] = vals_u16[:, s, :, sub, lane, 2 * k + 1].reshape(-1)
+                    nib[rows, g] = ((idx_u32[:, s, :, lane] >> (16 * sub + 4 * k)) & 0xF).reshape(-1)
+    gather = buf[g_off:g_off + T * Kp * 4].copy().view(np.int32).reshape(T, Kp)
+    out_rows = buf[o_off:o_off + M * 4].copy().view(np.int32)
+    zeros = buf[z_off:z_off + 1024]
+    return vals, nib, gather, out_rows, zeros
+
+
+@pytest.mark.parametrize("M,K,V,Kv,dtype", [(128, 256, 32, 128, "f16"), (256, 320, 128, 200, "bf16"),
+                                            (192, 256, 96, 64, "f16")])
+def test_prepared_buffer_is_a_reordering(M, K, V, Kv, dtype):
+    from tests import gpu_util as gu
+    case = synth.small_case(M, K, V, Kv, 8, dtype, 80)
+    vals, nm, vec = orc.pack(case.weights(), dtype, V, Kv)
+    p = gu.upload_packed(M, K, V, Kv, dtype, vals, nm, vec)
+    pin, pout = case.pi_in(), case.pi_out()
+    pr = gu.gpu_prepare(p, pin, pout)
+    v2, nib, gather, out_rows, zeros = _unswizzle(pr.buf.cpu().numpy(), M, K, V, Kv)
+    G = Kv // 4
+    assert np.array_equal(v2[:, :2 * G], vals)
+    assert np.all(v2[:, 2 * G:] == 0)
+    want_nib = np.stack([nm & 0xF, nm >> 4], axis=-1).reshape(M, G)
+    assert np.array_equal(nib[:, :G], want_nib)
+    assert np.all(nib[:, G:] == 0x4)
+    assert np.array_equal(gather[:, :Kv], pin[vec])
+    assert np.all(gather[:, Kv:] == -1)
+    assert np.array_equal(out_rows, pout)
+    assert np.all(zeros == 0)
+    pr = gu.gpu_prepare(p, None, None)
+    _, _, gather, out_rows, _ = _unswizzle(pr.buf.cpu().numpy(), M, K, V, Kv)
+    assert np.array_equal(gather[:, :Kv], vec) and np.array_equal(out_rows, np.arange(M))
+
+
+def _check(case, N, variants, relu=False, identity=False):
+    from tests import gpu_util as gu
+    vals, nm, vec = orc.pack(case.weights(), case.dtype, case.V, case.Kv)
+    Wh = orc.unpack_fast(vals, nm, vec, case.M, case.K, case.V)
+    Xb = case.activations(N)
+    pin = None if identity else case.pi_in()
+    pout = None if identity else case.pi_out()
+    Y_acc = orc.product(Wh, Xb, case.dtype, pin, pout, relu=relu).astype(np.float64)
+    p = gu.upload_packed(case.M, case.K, case.V, case.Kv, case.dtype, vals, nm, vec)
+    pr = gu.gpu_prepare(p, pin, pout)
+    f = RELU if relu else 0
+    for v in variants:
+        got32 = gu.gpu_spmm_prepared(pr, Xb, f | OUT_F32, variant=v).astype(np.float64)
+        gu.check_close(got32, Y_acc, what=f"{case.name} variant {v} fp32")
+        got = gu.gpu_spmm_prepared(pr, Xb, f, variant=v)
+        assert np.array_equal(got, orc.round_to_storage(got32.astype(np.float32), case.dtype)), f"variant {v}"
+        if case.dtype == "f16":
+            gu.check_close(orc.decode(got, "f16"), Y_acc, what=f"{case.name} variant {v} fp16")
+        else:
+            want = orc.decode(orc.round_to_storage(Y_acc.astype(np.float32), "bf16"), "bf16")
+            gotd = orc.decode(got, "bf16")
+            assert np.all(np.abs(gotd - want) <= np.maximum(1e-2, _ulp_bf16(want)))
+            gu.check_close(gotd, want, max_abs=np.inf, what=f"{case.name} variant {v} bf16")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("M,K,V,Kv,N", [
+    (128, 256, 32, 128, 37),
+    (128, 320, 64, 160, 300),     # ragged column tail inside the second 256-column block
+    (384, 512, 128, 256, 520),    # ragged tail past one 512-column block
+    (192, 256, 96, 64, 40),
+    (128, 512, 64, 200, 72),      # Kv % 64 != 0: padded kept columns
+    (256, 1024, 128, 704, 256),   # 11 steps: odd number of 64-column steps
+])
+def test_prepared_small_all_variants(M, K, V, Kv, N, dtype):
+    _check(synth.small_case(M, K, V, Kv, N, dtype, 81), N, VARIANTS)
+
+
+def test_prepared_relu_identity():
+    case = synth.small_case(128, 256, 64, 128, 72, "f16", 82)
+    _check(case, 72, [0, 2, 3], relu=True)
+    _check(case, 72, [0, 2, 3], identity=True)
+
+
+def test_prepared_c2_full():
+    c = synth.c2()
+    _check(c, c.N, [0, 2, 3, 4])
