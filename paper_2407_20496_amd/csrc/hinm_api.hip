@@ -218,7 +218,7 @@ hinm_status hinm_spmm_prepared_workspace(const hinm_shape* shape, int32_t N, siz
   if (st != HINM_OK) return st;
   if (!workspace_bytes) return HINM_ERR_NULL;
   if (N <= 0) return HINM_ERR_SHAPE;
-  *workspace_bytes = 0;
+  *workspace_bytes = (N <= 32) ? skinny_prepared_workspace_bytes(*shape, N) : 0;
   return HINM_OK;
 }
 
@@ -229,7 +229,7 @@ static hinm_status check_prepared_call(const hinm_shape* shape, int32_t N, const
   if (st != HINM_OK) return st;
   if (!prepared || !X || !Y) return HINM_ERR_NULL;
   if (N <= 0 || ldx < N || ldy < N) return HINM_ERR_SHAPE;
-  if (ldx % 8 != 0 || ldy % 8 != 0) return HINM_ERR_SHAPE;
+  if (N > 1 && (ldx % 8 != 0 || ldy % 8 != 0)) return HINM_ERR_SHAPE;
   if (!aligned(prepared, 256) || !aligned(X, 16) || !aligned(Y, 16)) return HINM_ERR_SHAPE;
   if (flags & ~(uint32_t)(HINM_EPI_RELU | HINM_OUT_F32 | HINM_VARIANT_MASK)) return HINM_ERR_UNSUPPORTED;
   return HINM_OK;
@@ -240,7 +240,15 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
                                 hipStream_t stream) {
   PreparedArgs a{*shape, N, prepared, X, ldx, Y, ldy, (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0,
                  (int)((flags & HINM_VARIANT_MASK) >> HINM_VARIANT_SHIFT), workspace, workspace_bytes};
-  hipError_t e = launch_spmm_tile_prepared(a, stream);
+  hipError_t e;
+  if (N <= 32 && a.tile_variant == 0) {
+    const size_t need = skinny_prepared_workspace_bytes(*shape, N);
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned(workspace, 256))) return HINM_ERR_WORKSPACE;
+    e = launch_spmm_skinny_prepared(a, stream);
+  } else {
+    if (N == 1 || ldx % 8 != 0 || ldy % 8 != 0) return HINM_ERR_UNSUPPORTED;
+    e = launch_spmm_tile_prepared(a, stream);
+  }
   return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 

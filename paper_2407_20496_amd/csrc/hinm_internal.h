@@ -84,5 +84,8 @@ struct PreparedArgs {
 };
 
 hipError_t launch_spmm_tile_prepared(const PreparedArgs& a, hipStream_t stream);
+// few columns (N <= 32): whole-tile workgroups, kept columns split over workgroups
+size_t skinny_prepared_workspace_bytes(const hinm_shape& s, int N);
+hipError_t launch_spmm_skinny_prepared(const PreparedArgs& a, hipStream_t stream);
 
 }  // namespace hinm

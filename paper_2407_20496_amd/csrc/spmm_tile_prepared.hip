@@ -347,9 +347,20 @@ hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// By shape: wide column blocks halve the re-reads of the stored values when there are enough of
+// them to fill the chip; short k loops prefer small stages so that several workgroups share a
+// compute unit and cover each other's start-up and epilogue.
+inline int choose_variant(const PreparedArgs& a) {
+  const PreparedLayout L = prepared_layout(a.s);
+  const int64_t wide_blocks = (int64_t)L.T * ((a.N + 511) / 512);
+  if (a.N >= 1024 && wide_blocks >= 256) return 3;  // 512 columns, 64-column stages, 2 deep
+  if (L.S <= 8) return 8;                           // 256 columns, 32-column stages, 2 deep
+  return 1;                                         // 256 columns, 64-column stages, 2 deep
+}
+
 template <int DT, int RB>
 hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
-  switch (a.tile_variant) {
+  switch (a.tile_variant ? a.tile_variant : choose_variant(a)) {
     case 1: return launch_cfg<DT, RB, 256, 2, 2>(a, stream);
     case 2: return launch_cfg<DT, RB, 256, 2, 3>(a, stream);
     case 3: return launch_cfg<DT, RB, 512, 2, 2>(a, stream);
@@ -357,6 +368,8 @@ hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
     case 5: return launch_cfg<DT, RB, 256, 1, 4>(a, stream);
     case 6: return launch_cfg<DT, RB, 512, 1, 3>(a, stream);
     case 7: return launch_cfg<DT, RB, 512, 1, 4>(a, stream);
+    case 8: return launch_cfg<DT, RB, 256, 1, 2>(a, stream);
+    case 9: return launch_cfg<DT, RB, 512, 1, 2>(a, stream);
     default: break;
   }
   return launch_cfg<DT, RB, 256, 2, 3>(a, stream);

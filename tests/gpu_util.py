@@ -115,8 +115,8 @@ def gpu_prepare(p: Packed, pi_in, pi_out) -> Prepared:
 def gpu_spmm_prepared(pr: Prepared, X_bits: np.ndarray, flags=0, variant=0, ldx=None, ldy=None, X_dev=None):
     p = pr.p
     K, N = X_bits.shape
-    ldx = ldx or (N + 7) // 8 * 8
-    ldy = ldy or (N + 7) // 8 * 8
+    ldx = ldx or (1 if N == 1 else (N + 7) // 8 * 8)
+    ldy = ldy or (1 if N == 1 else (N + 7) // 8 * 8)
     if X_dev is None:
         Xp = np.zeros((K, ldx), dtype=np.uint16)
         Xp[:, :N] = X_bits

@@ -123,3 +123,47 @@ def test_prepared_relu_identity():
 def test_prepared_c2_full():
     c = synth.c2()
     _check(c, c.N, [0, 2, 3, 4])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("M,K,V,Kv,N", [
+    (128, 256, 32, 128, 1),
+    (256, 1024, 128, 704, 16),    # several workgroups per tile, odd number of steps
+    (128, 2048, 64, 1032, 3),     # padded kept columns (Kv % 64 != 0)
+    (192, 512, 96, 256, 17),
+    (256, 4096, 128, 2048, 32),
+    (128, 512, 128, 64, 8),       # a single step: no split
+])
+def test_prepared_few_columns(M, K, V, Kv, N, dtype):
+    _check(synth.small_case(M, K, V, Kv, N, dtype, 83), N, [0])
+
+
+def test_prepared_few_columns_repeatable_and_needs_no_workspace():
+    # partial tiles are added in a fixed order: repeated calls give identical bits
+    import torch
+    from tests import gpu_util as gu
+    import paper_2407_20496_amd as hinm
+    case = synth.small_case(256, 2048, 128, 1024, 16, "bf16", 84)
+    vals, nm, vec = orc.pack(case.weights(), "bf16", 128, 1024)
+    p = gu.upload_packed(256, 2048, 128, 1024, "bf16", vals, nm, vec)
+    pr = gu.gpu_prepare(p, case.pi_in(), case.pi_out())
+    assert hinm.hinm_spmm_prepared_workspace(256, 2048, 128, 1024, "bf16", 16) == 0
+    Xd = gu.dev_bits(case.activations())
+    outs = []
+    for _ in range(3):
+        Y = torch.zeros((256, 16), dtype=torch.int16, device=gu.DEV)
+        hinm.hinm_spmm_prepared(256, 2048, 128, 1024, "bf16", 16, pr.buf, Xd, 16, Y, 16, 0, None, 0)
+        torch.cuda.synchronize()
+        outs.append(gu.host_bits(Y))
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    Wh = orc.unpack_fast(vals, nm, vec, 256, 2048, 128)
+    want = orc.product(Wh, case.activations(), "bf16", case.pi_in(), case.pi_out()).astype(np.float64)
+    got = orc.decode(outs[0], "bf16")
+    assert np.all(np.abs(got - want) <= np.maximum(1e-2, _ulp_bf16(want)))
+
+
+@pytest.mark.parametrize("idx", [0, 1, 3, 4, 6, 7, 9, 10])
+def test_prepared_c3_decode_full(idx):
+    c = synth.c3_cases()[idx]
+    assert c.N in (1, 16)
+    _check(c, c.N, [0])
