@@ -49,7 +49,8 @@ __global__ __launch_bounds__(256) void prepare_tables_kernel(const int32_t* __re
                                                              const int32_t* __restrict__ pi_in,
                                                              const int32_t* __restrict__ pi_out,
                                                              int32_t* __restrict__ gather, int32_t* __restrict__ out_rows,
-                                                             uint32_t* __restrict__ zeros, int T, int Kv, int Kp, int M) {
+                                                             uint32_t* __restrict__ zeros, uint32_t* __restrict__ panel,
+                                                             int T, int Kv, int Kp, int M, int K) {
   const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t n_gather = (int64_t)T * Kp;
   if (id < n_gather) {
@@ -60,6 +61,7 @@ __global__ __launch_bounds__(256) void prepare_tables_kernel(const int32_t* __re
       if (pi_in) g = pi_in[g];
     }
     gather[id] = g;
+    panel[id] = panel_entry_of_row(g, K);
   }
   if (id < M) out_rows[id] = pi_out ? pi_out[id] : (int32_t)id;
   if (id < kPrepZeroBytes / 4) zeros[id] = 0;
@@ -81,8 +83,8 @@ hipError_t launch_prepare(const hinm_shape& s, const void* vals, const uint8_t* 
   if (n < kPrepZeroBytes / 4) n = kPrepZeroBytes / 4;
   prepare_tables_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(
       vec_idx, pi_in, pi_out, reinterpret_cast<int32_t*>(base + L.gather_offset),
-      reinterpret_cast<int32_t*>(base + L.pi_out_offset), reinterpret_cast<uint32_t*>(base + L.zero_offset), L.T,
-      s.Kv, L.Kp, s.M);
+      reinterpret_cast<int32_t*>(base + L.pi_out_offset), reinterpret_cast<uint32_t*>(base + L.zero_offset),
+      reinterpret_cast<uint32_t*>(base + L.panel_offset), L.T, s.Kv, L.Kp, s.M, s.K);
   return hipGetLastError();
 }
 

@@ -16,6 +16,10 @@
 //                             pi_in); -1 for padded j
 //     pi_out  int32 [M]       row of Y that row r of the layer writes
 //     zeros   1024 bytes      an all-zero row segment (source of padded / out-of-range copies)
+//     panel   uint32 [T][Kp]  the same gather table as LDS byte addresses for the kernel that keeps a
+//                             64-column panel of X (all K rows, 128 bytes each) in LDS: row g sits at
+//                             128 g with its 32-byte units XOR-swizzled by bit 1 of g, so the entry is
+//                             128 g | ((g & 2) << 5); padded j point at the all-zero row 8 ceil(K / 8)
 #pragma once
 
 #include <stddef.h>
@@ -31,7 +35,7 @@ constexpr int kPrepZeroBytes = 1024;
 
 struct PreparedLayout {
   int T, RB, S, Kp;
-  size_t a_offset, gather_offset, pi_out_offset, zero_offset, total_bytes;
+  size_t a_offset, gather_offset, pi_out_offset, zero_offset, panel_offset, total_bytes;
 };
 
 __host__ __device__ inline size_t prep_align256(size_t x) { return (x + 255) / 256 * 256; }
@@ -46,8 +50,14 @@ __host__ inline PreparedLayout prepared_layout(const hinm_shape& s) {
   L.gather_offset = prep_align256((size_t)L.T * L.S * L.RB * kPrepBlockBytes);
   L.pi_out_offset = L.gather_offset + prep_align256((size_t)L.T * L.Kp * 4);
   L.zero_offset = L.pi_out_offset + prep_align256((size_t)s.M * 4);
-  L.total_bytes = L.zero_offset + kPrepZeroBytes;
+  L.panel_offset = L.zero_offset + kPrepZeroBytes;
+  L.total_bytes = L.panel_offset + prep_align256((size_t)L.T * L.Kp * 4);
   return L;
+}
+
+__host__ __device__ inline uint32_t panel_entry_of_row(int g, int K) {
+  const uint32_t row = (g >= 0) ? (uint32_t)g : (uint32_t)((K + 7) / 8 * 8);
+  return (row << 7) | ((g >= 0) ? (((uint32_t)g & 2u) << 5) : 0u);
 }
 
 }  // namespace hinm

@@ -9,7 +9,7 @@ from oracle import hinm_oracle as orc
 pytestmark = pytest.mark.gpu
 
 OUT_F32, RELU = 2, 1
-VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7]
+VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 15]   # 15 = LDS-resident panel kernel (small K only)
 
 
 def _ulp_bf16(y):
@@ -48,6 +48,11 @@ def _unswizzle(buf: np.ndarray, M, K, V, Kv):
     gather = buf[g_off:g_off + T * Kp * 4].copy().view(np.int32).reshape(T, Kp)
     out_rows = buf[o_off:o_off + M * 4].copy().view(np.int32)
     zeros = buf[z_off:z_off + 1024]
+    panel = buf[z_off + 1024:z_off + 1024 + T * Kp * 4].copy().view(np.uint32).reshape(T, Kp)
+    K8 = (K + 7) // 8 * 8
+    g = gather.astype(np.int64)
+    want_panel = np.where(g >= 0, (g << 7) | ((g & 2) << 5), K8 << 7).astype(np.uint32)
+    assert np.array_equal(panel, want_panel), "LDS-address form of the gather table"
     return vals, nib, gather, out_rows, zeros
 
 
@@ -87,8 +92,14 @@ def _check(case, N, variants, relu=False, identity=False):
     p = gu.upload_packed(case.M, case.K, case.V, case.Kv, case.dtype, vals, nm, vec)
     pr = gu.gpu_prepare(p, pin, pout)
     f = RELU if relu else 0
+    import paper_2407_20496_amd as hinm
     for v in variants:
-        got32 = gu.gpu_spmm_prepared(pr, Xb, f | OUT_F32, variant=v).astype(np.float64)
+        try:
+            got32 = gu.gpu_spmm_prepared(pr, Xb, f | OUT_F32, variant=v).astype(np.float64)
+        except hinm.HinmError as err:
+            # the panel kernel refuses shapes whose panel does not fit in LDS; nothing else may refuse
+            assert v == 15 and err.status == 5 and (((case.K + 7) // 8 * 8 + 8) * 128 + 8 * 32 * 144 > 160 * 1024 or N <= 32)
+            continue
         gu.check_close(got32, Y_acc, what=f"{case.name} variant {v} fp32")
         got = gu.gpu_spmm_prepared(pr, Xb, f, variant=v)
         assert np.array_equal(got, orc.round_to_storage(got32.astype(np.float32), case.dtype)), f"variant {v}"
@@ -122,7 +133,14 @@ def test_prepared_relu_identity():
 
 def test_prepared_c2_full():
     c = synth.c2()
-    _check(c, c.N, [0, 2, 3, 4])
+    _check(c, c.N, [0, 1, 3, 8, 15])
+
+
+def test_prepared_panel_kernel_edges():
+    # K not a multiple of 8, ragged N, padded kept columns, one tile per wave and fewer tiles than waves
+    _check(synth.small_case(64, 100, 32, 40, 70, "f16", 85), 70, [15])
+    _check(synth.small_case(96, 1000, 32, 504, 130, "bf16", 86), 130, [15], relu=True)
+    _check(synth.small_case(64, 512, 64, 256, 64, "f16", 87), 64, [15], identity=True)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
