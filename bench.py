@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="pin a tile-kernel configuration (tuning aid)")
     ap.add_argument("--sets", type=int, default=None,
                     help="number of rotated buffer sets (default: enough to exceed the Infinity Cache)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step from the host instead of replaying one captured HIP graph of K steps")
     args = ap.parse_args()
@@ -226,13 +228,34 @@ def main():
         roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / MFMA_DENSE_PEAK_TFLOPS, 4), "traffic": None}
     if use_prepared:
-        roofline["kernel"] = "spmm_tile_prepared_kernel"
+        k8 = (c.K + 7) // 8 * 8
+        panel_fits = (k8 + 8) * 128 + 8 * 32 * 144 <= 160 * 1024
+        roofline["kernel"] = ("spmm_skinny_prepared_kernel" if N <= 32 else
+                              "spmm_panel_prepared_kernel" if (panel_fits and args.variant in (0, 15)) else
+                              "spmm_tile_prepared_kernel")
     else:
         roofline["kernel"] = "spmm_skinny_kernel" if N <= 16 or c.V % 32 else "spmm_tile_kernel"
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            tr = json.load(f).get(args.workload if not args.canonical else args.workload + "-canonical")
+        if tr and mem_bound:
+            roofline["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
+            roofline["traffic_source"] = tr.get("source")
+    except (OSError, ValueError):
+        pass
     roofline["kernel_ms_avg"] = round(kernel_ms, 6)
     roofline["kernel_ms_median_event_pair"] = round(kernel_ms_med, 6)
     roofline["algorithmic_bytes_per_launch"] = bytes_step // n_layers
     roofline["stored_value_flops_per_launch"] = flops_stored / n_layers
+
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.bitwise_not(src, out=dst)   # an elementwise kernel of its own: reads and writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- same-shape dense GEMM (library) on the same tensors, same timing method ---------------
     dense = None

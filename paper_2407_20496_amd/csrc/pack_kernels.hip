@@ -79,6 +79,9 @@ __device__ __forceinline__ uint32_t block_exclusive_count(bool flag, uint32_t* w
   return before + in_wave;
 }
 
+// KPT = keys per thread held in registers for the whole kernel (K <= KPT * 1024), or 0 = re-read
+// the keys from memory in every pass (any K).
+template <int KPT>
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __restrict__ scores,
                                                                 int32_t* __restrict__ vec_idx, int K, int Kv) {
   __shared__ uint32_t hist[256];
@@ -87,27 +90,78 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
   __shared__ uint32_t s_need;
   const int t = blockIdx.x;
   const unsigned long long* key = reinterpret_cast<const unsigned long long*>(scores + (size_t)t * K);
+  constexpr int kHeld = KPT > 0 ? KPT : 1;
+  unsigned long long held[kHeld];
+  if constexpr (KPT > 0) {
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      const int k = c * kSelectThreads + threadIdx.x;
+      held[c] = (k < K) ? key[k] : 0ull;
+    }
+  }
+  const int chunks = KPT > 0 ? KPT : (K + kSelectThreads - 1) / kSelectThreads;
 
   unsigned long long prefix = 0, mask = 0;
   uint32_t need = (uint32_t)Kv;  // the need-th largest among keys that match prefix under mask
   for (int shift = 56; shift >= 0; shift -= 8) {
     if (threadIdx.x < 256) hist[threadIdx.x] = 0;
     __syncthreads();
-    for (int k = threadIdx.x; k < K; k += kSelectThreads) {
-      const unsigned long long u = key[k];
-      if ((u & mask) == prefix) atomicAdd(&hist[(uint32_t)(u >> shift) & 255u], 1u);
+#pragma unroll
+    for (int c = 0; c < chunks; ++c) {
+      const int k = c * kSelectThreads + threadIdx.x;
+      unsigned long long u;
+      if constexpr (KPT > 0) u = held[c];
+      else u = (k < K) ? key[k] : 0ull;
+      bool pending = (k < K) && ((u & mask) == prefix);
+      const uint32_t d = (uint32_t)(u >> shift) & 255u;
+      // Scores of one tile share their leading bits, so in the first passes nearly every lane hits the
+      // same bin: count the two most common digits of the wave with one atomic each, the rest singly.
+#pragma unroll
+      for (int round = 0; round < 2; ++round) {
+        const unsigned long long todo = __ballot(pending);
+        if (todo == 0ull) break;
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t dl = (uint32_t)__shfl((int)d, leader);
+        const unsigned long long same = __ballot(pending && d == dl);
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[dl], (uint32_t)__popcll(same));
+        pending = pending && d != dl;
+      }
+      if (pending) atomicAdd(&hist[d], 1u);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t cum = 0;
-      int d = 255;
-      for (; d > 0; --d) {
-        const uint32_t h = hist[d];
-        if (cum + h >= need) break;
-        cum += h;
+    // Find the digit that holds the need-th largest key: the first wave scans the 256 bins from the
+    // top, four bins per lane (lane 0 owns the highest four).
+    if (threadIdx.x < 64) {
+      const int lane = threadIdx.x;
+      uint32_t h[4];
+      uint32_t mine = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        h[q] = hist[255 - (4 * lane + q)];
+        mine += h[q];
       }
-      s_prefix = prefix | ((unsigned long long)d << shift);
-      s_need = need - cum;
+      uint32_t incl = mine;  // inclusive prefix over lanes = keys in this lane's bins or higher ones
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t v = (uint32_t)__shfl_up((int)incl, off);
+        if (lane >= off) incl += v;
+      }
+      uint32_t above = incl - mine;  // keys in strictly higher lanes' bins
+      const bool here = (above < need) && (incl >= need);
+      const bool nowhere = (__ballot(here) == 0ull);  // fewer keys than asked for: cannot happen for Kv <= K
+      if (here || (nowhere && lane == 63)) {
+        int pick = 3;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (above + h[q] >= need) {
+            pick = q;
+            break;
+          }
+          above += h[q];
+        }
+        s_prefix = prefix | ((unsigned long long)(255 - (4 * lane + pick)) << shift);
+        s_need = need - above;
+      }
     }
     __syncthreads();
     prefix = s_prefix;
@@ -119,10 +173,13 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
 
   uint32_t eq_base = 0, kept_base = 0;
   int32_t* out = vec_idx + (size_t)t * Kv;
-  for (int k0 = 0; k0 < K; k0 += kSelectThreads) {
-    const int k = k0 + threadIdx.x;
+#pragma unroll
+  for (int c = 0; c < chunks; ++c) {
+    const int k = c * kSelectThreads + threadIdx.x;
     const bool in = k < K;
-    const unsigned long long u = in ? key[k] : 0ull;
+    unsigned long long u;
+    if constexpr (KPT > 0) u = held[c];
+    else u = in ? key[k] : 0ull;
     const bool gt = in && u > tau;
     const bool eq = in && u == tau;
     uint32_t eq_total, kept_total;
@@ -233,7 +290,9 @@ hipError_t launch_pack(const hinm_shape& s, const void* W, void* vals, uint8_t* 
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  select_kernel<<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
+  if (s.K <= 4 * kSelectThreads) select_kernel<4><<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
+  else if (s.K <= 16 * kSelectThreads) select_kernel<16><<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
+  else select_kernel<0><<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t emit_threads = (int64_t)s.M * (s.Kv / 8);
