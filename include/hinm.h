@@ -78,8 +78,9 @@ enum {
   HINM_OUT_F32 = 2u,          /* Y is float32 [M][N]: the un-rounded accumulators (verification mode) */
   /* kernel choice; default (none set) picks by shape */
   HINM_KERNEL_REFERENCE = 0x100u, /* one thread per output element, plain FMA; any V */
-  HINM_KERNEL_SMFMAC = 0x200u,    /* sparse-MFMA tile kernel; needs V in {16,32,64,96,128} */
-  HINM_KERNEL_GEMV = 0x400u,      /* k-split skinny kernel; N <= 16 */
+  HINM_KERNEL_SMFMAC = 0x200u,    /* a sparse-MFMA kernel: 32x32 tiles (V in {32,64,96,128}, Kv % 32 == 0,
+                                     ld % 8 == 0) or else the 16-column form (V % 16 == 0) */
+  HINM_KERNEL_GEMV = 0x400u,      /* 16-column sparse-MFMA form with k split over the waves; N <= 16, V % 16 == 0 */
   /* hinm_spmm_prepared only, tuning aid: bits 16..19 pin one kernel configuration (0 = by shape) */
   HINM_VARIANT_SHIFT = 16,
   HINM_VARIANT_MASK = 0xF0000u
@@ -139,12 +140,12 @@ hinm_status hinm_prepare(const hinm_shape* shape, const void* vals, const uint8_
 
 /* Same product as hinm_spmm, computed from a prepared layer (its pi_in / pi_out are the ones given
  * to hinm_prepare).  Flags: HINM_EPI_RELU, HINM_OUT_F32.
- * Few-column shapes (N <= 32) split each tile's kept columns over several workgroups, which leave
- * fp32 partial tiles in `workspace`; the workgroup that finishes a tile last adds them up in a
- * fixed order, so results are reproducible.  hinm_spmm_prepared_workspace gives the bytes needed
- * (0 for shapes that need none).  The workspace is 256-byte aligned device memory that the CALLER
- * ZERO-FILLS ONCE before its first use; every call returns it zero-filled where it must be, so it
- * can be reused by later calls on the same stream, but not by calls that may overlap in time. */
+ * Few-column shapes (N <= 32) split each tile's kept columns over the waves of one workgroup,
+ * which add their fp32 partial tiles in LDS in a fixed order, so results are reproducible bit for bit.
+ * hinm_spmm_prepared_workspace gives the bytes of device workspace a shape needs: 0 for every kernel
+ * of this build, so `workspace` may be NULL (the argument stays in the ABI for kernels that split a
+ * tile over workgroups; one that needs it returns HINM_ERR_WORKSPACE when it is missing, misaligned
+ * (256 bytes) or too small). */
 hinm_status hinm_spmm_prepared_workspace(const hinm_shape* shape, int32_t N, size_t* workspace_bytes);
 hinm_status hinm_spmm_prepared(const hinm_shape* shape, int32_t N, const void* prepared,
                                const void* X, int64_t ldx, void* Y, int64_t ldy, uint32_t flags,
