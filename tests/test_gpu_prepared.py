@@ -151,6 +151,8 @@ def test_prepared_panel_kernel_edges():
     (192, 512, 96, 256, 17),
     (256, 4096, 128, 2048, 32),
     (128, 512, 128, 64, 8),       # a single step: no split
+    (64, 4224, 32, 2200, 1),      # one column, more than 32 steps: the input vector is staged in LDS; padded steps
+    (64, 4220, 32, 2112, 1),      # K % 8 != 0: same shape class without staging
 ])
 def test_prepared_few_columns(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 83), N, [0])
