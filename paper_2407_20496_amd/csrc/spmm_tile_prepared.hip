@@ -74,17 +74,23 @@ struct TileCfg {
   static constexpr int KS = 32 * KSUB;
   static constexpr int ROW_BYTES = NB * 2;
   static constexpr int B_BYTES = KS * ROW_BYTES;
-  static constexpr int A_RB_BYTES = KSUB * 1024 + 256;          // per row block: values of KSUB substeps + nibbles
-  static constexpr int A_GRANULES = RB * (KSUB * 64 + 16);
+  static constexpr int STEPS = (KSUB + 1) / 2;                   // 64-column steps per stage (KSUB = 1: half a step)
+  static constexpr int SUBS = KSUB / STEPS;                      // 32-column substeps per step and stage
+  static constexpr int A_RB_BYTES = SUBS * 1024 + 256;           // per step and row block: values of its substeps + nibbles
+  static constexpr int A_GRANULES = STEPS * RB * (SUBS * 64 + 16);
   static constexpr int A_INSTR = (A_GRANULES + 63) / 64;         // wave-wide copies for A per stage
   static constexpr int A_BYTES = A_INSTR * 1024;                 // rounded up: the last copy may overshoot
-  static constexpr int STAGE_BYTES = B_BYTES + A_BYTES;
+  // LDS: ST buffers for the gathered rows (B), then ST buffers for the stored values (A).  (Requesting
+  // the A chunk one stage earlier than its rows, with a third A buffer, was measured slower on every
+  // shape: 5 to 10 %.)
+  static constexpr int STAGES_BYTES = ST * (B_BYTES + A_BYTES);
   static constexpr int B_PER_WAVE = (NB == 512 ? KS : KS / 2) / NW;  // wave-wide copies for B per wave and stage
   static constexpr int ROWS_PER_WAVE = KS / NW;
   static constexpr int Y_STRIDE = NB * 2 + 16;
   static constexpr int EPI_BYTES = 32 * RB * Y_STRIDE;
-  static constexpr int LDS_BYTES = (ST * STAGE_BYTES > EPI_BYTES) ? ST * STAGE_BYTES : EPI_BYTES;
+  static constexpr int LDS_BYTES = (STAGES_BYTES > EPI_BYTES) ? STAGES_BYTES : EPI_BYTES;
   static_assert(NB == 256 || NB == 512, "column block");
+  static_assert(KSUB == 1 || KSUB == 2 || KSUB == 4, "half a step, one step or two steps per stage");
   static_assert(B_PER_WAVE == 4 * KSUB, "copy split");
   static_assert(ST >= 2 && ST <= 4 && (A_INSTR + NW - 1) / NW <= 3, "wait table covers these");
 };
@@ -114,7 +120,7 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int stages_total = S64 * (2 / KSUB);  // stages of KS columns
+  const int stages_total = (KSUB == 4) ? S64 / 2 : S64 * (2 / KSUB);  // stages of KS columns (KSUB = 4: S64 is even)
   const int Kp = S64 * 64;
 
   const int32_t* gt = gather + (size_t)t * Kp;
@@ -146,7 +152,7 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
 #pragma unroll
   for (int m = 0; m < A_ROUNDS; ++m) {
     const int gran = min((wave + m * NW) * 64 + lane, C::A_GRANULES - 1);  // overshoot re-reads the last granule
-    if constexpr (KSUB == 2) {
+    if constexpr (KSUB >= 2) {
       a_src_off[m] = gran * 16;
       a_src_odd_stage[m] = 0;
     } else {
@@ -165,7 +171,10 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
   auto row_base = [&](int g) -> const uint8_t* {  // wave-uniform
     return (g >= 0) ? x_block + (size_t)g * ldx * 2 : zeros;
   };
-  auto issue_stage = [&](int stage_idx, uint8_t* stage, const rows_t rows) {
+  auto b_buffer = [&](int stage_idx) -> uint8_t* { return lds + (stage_idx % ST) * C::B_BYTES; };
+  auto a_buffer = [&](int stage_idx) -> uint8_t* { return lds + ST * C::B_BYTES + (stage_idx % ST) * C::A_BYTES; };
+  auto issue_b = [&](int stage_idx, const rows_t rows) {
+    uint8_t* stage = b_buffer(stage_idx);
 #pragma unroll
     for (int k = 0; k < C::B_PER_WAVE; ++k) {
       if constexpr (NB == 512) {
@@ -177,8 +186,10 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
         copy16_to_lds(src, stage + (wave * C::ROWS_PER_WAVE + 2 * k) * C::ROW_BYTES);
       }
     }
-    uint8_t* a_lds = stage + C::B_BYTES;
-    const uint8_t* a_stage = (KSUB == 2) ? a_tile + (size_t)stage_idx * RB * kPrepBlockBytes
+  };
+  auto issue_a = [&](int stage_idx) {
+    uint8_t* a_lds = a_buffer(stage_idx);
+    const uint8_t* a_stage = (KSUB >= 2) ? a_tile + (size_t)stage_idx * C::STEPS * RB * kPrepBlockBytes
                                          : a_tile + (size_t)(stage_idx >> 1) * RB * kPrepBlockBytes;
 #pragma unroll
     for (int m = 0; m < A_ROUNDS; ++m) {
@@ -215,17 +226,21 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
 
   // B slots 8 h + 4 u .. + 3 of lane group qb <- rows 16 h + 8 qb + 4 u + (0..3) of the substep
   auto read_b = [&](uint32_t stage_addr, int cb, auto sub_tag) -> u32x8 {
-    constexpr int SUB = decltype(sub_tag)::value;
-    constexpr int R0 = (SUB * 32 + 0) * C::ROW_BYTES, R1 = (SUB * 32 + 4) * C::ROW_BYTES,
-                  R2 = (SUB * 32 + 16) * C::ROW_BYTES, R3 = (SUB * 32 + 20) * C::ROW_BYTES;
+    constexpr int Q = decltype(sub_tag)::value;  // 32-column substep of the stage
+    constexpr int R0 = (Q * 32 + 0) * C::ROW_BYTES, R1 = (Q * 32 + 4) * C::ROW_BYTES,
+                  R2 = (Q * 32 + 16) * C::ROW_BYTES, R3 = (Q * 32 + 20) * C::ROW_BYTES;
     u32x2 r0, r1, r2, r3;
     lds_read_tr16_x4<R0, R1, R2, R3>(stage_addr + b_lane_off[cb], r0, r1, r2, r3);
     return u32x8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
   };
 
-  auto compute_sub = [&](int stage_idx, const uint8_t* stage, auto sub_tag) {
-    constexpr int SUB = decltype(sub_tag)::value;
-    const uint8_t* as = stage + C::B_BYTES;
+  auto compute_sub = [&](int stage_idx, auto sub_tag) {
+    const uint8_t* stage = b_buffer(stage_idx);
+    // Q = 32-column substep of the stage; it belongs to step Q / SUBS of the stage and is substep
+    // SUB of that step (the substep picks the half of the step's index word, ABID)
+    constexpr int Q = decltype(sub_tag)::value;
+    constexpr int STEP = Q / C::SUBS, SUB = Q % C::SUBS;
+    const uint8_t* as = a_buffer(stage_idx);
     const uint32_t stage_addr = lds_base + (uint32_t)(stage - lds);
     u32x8 b0 = read_b(stage_addr, 0, sub_tag);
     u32x8 b1 = read_b(stage_addr, 1, sub_tag);
@@ -233,16 +248,16 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
     int idx[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      const uint8_t* blk = as + rb * C::A_RB_BYTES;
+      const uint8_t* blk = as + (STEP * RB + rb) * C::A_RB_BYTES;
       a[rb] = *reinterpret_cast<const u32x4*>(blk + SUB * 1024 + lane * 16);
-      idx[rb] = *reinterpret_cast<const int*>(blk + KSUB * 1024 + lane * 4);
+      idx[rb] = *reinterpret_cast<const int*>(blk + C::SUBS * 1024 + lane * 4);
       // the index register holds the nibbles of both substeps of a 64-column step
       if (KSUB == 1 && (stage_idx & 1)) idx[rb] = (int)((uint32_t)idx[rb] >> 16);
     }
     lds_wait_tr(b0, b1);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      if constexpr (KSUB == 2 && SUB == 1) {
+      if constexpr (SUB == 1) {
         acc[rb][0] = smfmac_32x32x32<DT, 1>(a[rb], b0, acc[rb][0], idx[rb]);
         acc[rb][1] = smfmac_32x32x32<DT, 1>(a[rb], b1, acc[rb][1], idx[rb]);
       } else {
@@ -251,15 +266,24 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
       }
     }
   };
-  auto compute_stage = [&](int stage_idx, const uint8_t* stage) {
-    compute_sub(stage_idx, stage, std::integral_constant<int, 0>{});
-    if constexpr (KSUB == 2) compute_sub(stage_idx, stage, std::integral_constant<int, 1>{});
+  auto compute_stage = [&](int stage_idx) {
+    compute_sub(stage_idx, std::integral_constant<int, 0>{});
+    if constexpr (KSUB >= 2) compute_sub(stage_idx, std::integral_constant<int, 1>{});
+    if constexpr (KSUB == 4) {
+      compute_sub(stage_idx, std::integral_constant<int, 2>{});
+      compute_sub(stage_idx, std::integral_constant<int, 3>{});
+    }
   };
 
   // ---- pipeline ---------------------------------------------------------------------------------------
+  // Issue order: B(0) A(0) B(1) A(1) ... up to the pipeline depth, then per iteration s the copies
+  // of stage s + ST - 1.  Copies complete in issue order.
 #pragma unroll
   for (int p = 0; p < ST - 1; ++p)
-    if (p < stages_total) issue_stage(p, lds + p * C::STAGE_BYTES, load_rows(p));
+    if (p < stages_total) {
+      issue_b(p, load_rows(p));
+      issue_a(p);
+    }
   rows_t rows_next = load_rows(ST - 1);
   for (int s = 0; s < stages_total; ++s) {
     // stage s must have landed; the stages issued after it may still be in flight
@@ -268,9 +292,12 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
     else wait_copies_outstanding<C::B_PER_WAVE>(later, extra_copies);
     __builtin_amdgcn_s_barrier();
     const int nxt = s + ST - 1;
-    if (nxt < stages_total) issue_stage(nxt, lds + (nxt % ST) * C::STAGE_BYTES, rows_next);
+    if (nxt < stages_total) {
+      issue_b(nxt, rows_next);
+      issue_a(nxt);
+    }
     rows_next = load_rows(nxt + 1);
-    compute_stage(s, lds + (s % ST) * C::STAGE_BYTES);
+    compute_stage(s);
   }
 
   // ---- epilogue -------------------------------------------------------------------------------------
@@ -355,6 +382,10 @@ inline int choose_variant(const PreparedArgs& a) {
   const int64_t wide_blocks = (int64_t)L.T * ((a.N + 511) / 512);
   if (a.N >= 1024 && wide_blocks >= 256) return 3;  // 512 columns, 64-column stages, 2 deep
   if (L.S <= 8) return 8;                           // 256 columns, 32-column stages, 2 deep
+  // At most one workgroup per compute unit: every stage then waits one full memory round trip, and
+  // 128-column stages halve the number of round trips.
+  const int64_t blocks = (int64_t)L.T * ((a.N + 255) / 256);
+  if (L.RB <= 2 && L.S % 2 == 0 && blocks <= 256) return 10;
   return 1;                                         // 256 columns, 64-column stages, 2 deep
 }
 
@@ -370,6 +401,11 @@ hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
     case 7: return launch_cfg<DT, RB, 512, 1, 4>(a, stream);
     case 8: return launch_cfg<DT, RB, 256, 1, 2>(a, stream);
     case 9: return launch_cfg<DT, RB, 512, 1, 2>(a, stream);
+    case 10:  // two 64-column steps per stage: needs an even number of steps and V <= 64 (LDS)
+      if constexpr (RB <= 2) {
+        if (prepared_layout(a.s).S % 2 == 0) return launch_cfg<DT, RB, 256, 4, 2>(a, stream);
+      }
+      break;
     default: break;
   }
   return launch_cfg<DT, RB, 256, 2, 3>(a, stream);
