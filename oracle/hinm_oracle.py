@@ -19,6 +19,10 @@ What it follows (arXiv 2407.20496):
     through the vector index composed with an input-channel order and writes
     output channels in the layer's own output-channel order, so the result is
     Y = P_out (W_HiNM (P_in X)).
+  * Section 3.2 ("tile-wise input channel permutation") and Section 4.2: the
+    kept column vectors of a tile may be arranged in a caller-given order before
+    the 2:4 step (tile_order, pack's sigma argument); the search that finds a
+    good order is not part of this file.
 
 Readings where the paper is silent (all repeated in the design notes):
   saliency of a V x 1 vector = sum of squares (L2), accumulated in binary64 in
@@ -34,8 +38,8 @@ Readings where the paper is silent (all repeated in the design notes):
 
 Pins: tests/test_oracle_*.py (brute-force enumeration of Eq. 2 / Eq. 3 on tiny
 inputs, exact kept counts, the sparsity formula, pack/unpack round trip,
-identity-permutation and dense-library reductions, the hand-derived example in
-tests/golden/).  The paper prints no numeric worked example for this path.
+identity-permutation and dense-library reductions, the hand-derived examples in
+tests/golden/, one of them with a tile-wise order).  The paper prints no numeric worked example for this path.
 """
 from __future__ import annotations
 
@@ -111,6 +115,25 @@ def vector_index(W_bits: np.ndarray, dtype: str, V: int, Kv: int) -> np.ndarray:
     return out
 
 
+def tile_order(vec_idx: np.ndarray, sigma: Optional[np.ndarray], K: int) -> np.ndarray:
+    """Tile-wise input-channel permutation (Section 3.2, "tile-wise input channel
+    permutation"; Section 4.2, the sigma_i^t of Eq. 4): the kept column vectors of tile t are
+    arranged in the order in which they appear in sigma[t], a permutation of all K input
+    channels given by the caller, instead of ascending column order.  Which columns are kept
+    does not change; which four of them form a 2:4 group does.  sigma None = ascending order."""
+    if sigma is None:
+        return vec_idx
+    sigma = np.asarray(sigma)
+    T, Kv = vec_idx.shape
+    assert sigma.shape == (T, K)
+    out = np.empty_like(vec_idx)
+    for t in range(T):
+        assert sorted(sigma[t].tolist()) == list(range(K)), "sigma[t] must be a permutation of the input channels"
+        kept = set(vec_idx[t].tolist())
+        out[t] = [c for c in sigma[t].tolist() if c in kept]
+    return out
+
+
 # --------------------------------------------------------------------------
 # Section 1 / Eq. 3 constraint: 2:4 selection on the surviving columns
 # --------------------------------------------------------------------------
@@ -125,14 +148,15 @@ def nm_positions(C: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     return kept[..., 0], kept[..., 1]
 
 
-def pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int):
+def pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, sigma: Optional[np.ndarray] = None):
     """Dense W (uint16 bits [M, K]) -> (vals uint16 [M, Kv/2], nm_idx uint8
-    [M, Kv/8], vec_idx int32 [T, Kv])."""
+    [M, Kv/8], vec_idx int32 [T, Kv]).  sigma (int [T, K], optional): per-tile order of the
+    input channels, see tile_order."""
     W_bits = np.ascontiguousarray(W_bits, dtype=np.uint16)
     M, K = W_bits.shape
     assert M % V == 0 and Kv % 8 == 0 and 0 < Kv <= K
     T = M // V
-    vec_idx = vector_index(W_bits, dtype, V, Kv)
+    vec_idx = tile_order(vector_index(W_bits, dtype, V, Kv), sigma, K)
     G = Kv // 4
     vals = np.empty((M, Kv // 2), dtype=np.uint16)
     nm_idx = np.empty((M, Kv // 8), dtype=np.uint8)

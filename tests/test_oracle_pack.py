@@ -76,3 +76,59 @@ def test_rounding_helpers_match_torch():
     assert np.array_equal(synth.to_bits(x[:20000], "bf16"), want_bf[:20000])
     back = torch.from_numpy(want_bf.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
     assert np.array_equal(orc.decode(want_bf, "bf16"), back, equal_nan=True)
+
+
+# ---- tile-wise order of the kept column vectors (Section 3.2; sigma_i^t of Section 4.2) ------------------
+
+def test_hand_example_with_tile_order(hand_example):
+    from tests.conftest import load_golden
+    ex, so = hand_example, load_golden("hand_example_v4_tile_order.txt")
+    for dtype in ("f16", "bf16"):
+        Wb = synth.to_bits(ex["W"].astype(np.float32), dtype)
+        vals, nm, vec = orc.pack(Wb, dtype, 4, 8, sigma=so["sigma"])
+        assert vec.tolist() == so["vec_idx"].tolist()
+        assert orc.decode(vals, dtype).tolist() == so["vals"].astype(np.float64).tolist()
+        assert nm.reshape(-1).tolist() == so["nm_idx"].reshape(-1).tolist()
+        Wh = orc.unpack(vals, nm, vec, 4, 16, 4)
+        Xb = synth.to_bits(ex["X"].astype(np.float32), dtype)
+        Y = orc.spmm(Wh, Xb, dtype, ex["pi_in"].reshape(-1), ex["pi_out"].reshape(-1))
+        assert orc.decode(Y, dtype).tolist() == so["Y"].astype(np.float64).tolist()
+
+
+def test_ascending_tile_order_is_the_plain_pack():
+    c = synth.small_case(64, 96, 16, 48, 4, "f16", 21)
+    Wb = c.weights()
+    ident = np.tile(np.arange(c.K), (c.T, 1))
+    for a, b in zip(orc.pack(Wb, c.dtype, c.V, c.Kv), orc.pack(Wb, c.dtype, c.V, c.Kv, sigma=ident)):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_tile_order_keeps_the_vector_mask_and_regroups(dtype):
+    c = synth.small_case(48, 40, 16, 24, 4, dtype, 22)
+    Wb = c.weights()
+    rng = np.random.default_rng(5)
+    sigma = np.stack([rng.permutation(c.K) for _ in range(c.T)])
+    _, _, plain = orc.pack(Wb, dtype, c.V, c.Kv)
+    vals, nm, vec = orc.pack(Wb, dtype, c.V, c.Kv, sigma=sigma)
+    W = orc.decode(Wb, dtype)
+    for t in range(c.T):
+        # the same columns survive, arranged as a subsequence of sigma[t]
+        assert sorted(vec[t].tolist()) == plain[t].tolist()
+        where = {ch: i for i, ch in enumerate(sigma[t].tolist())}
+        pos = [where[ch] for ch in vec[t].tolist()]
+        assert pos == sorted(pos)
+    # every group of four consecutive kept vectors (in that order) keeps its two largest magnitudes:
+    # brute force over the six pairs, the retained magnitude must be the maximum
+    m = orc.mask(nm, vec, c.M, c.K, c.V)
+    for r in range(c.M):
+        t = r // c.V
+        for g in range(c.Kv // 4):
+            cols = vec[t, 4 * g:4 * g + 4]
+            mags = np.abs(W[r, cols])
+            kept = m[r, cols]
+            assert kept.sum() == 2
+            best = max(mags[i] + mags[j] for i in range(4) for j in range(i + 1, 4))
+            assert mags[kept].sum() == best
+    # and unpack is still the masked matrix, bit for bit
+    assert np.array_equal(orc.unpack(vals, nm, vec, c.M, c.K, c.V), np.where(m, Wb, np.uint16(0)))
