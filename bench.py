@@ -79,11 +79,11 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
-    if args.workload == "pack-c5":
+    if args.workload in ("pack-c5", "pack-c5-ordered"):
         return bench_pack(args, torch, hinm, dev)
     wl = workloads()
     if args.workload not in wl:
-        print("unknown workload; choose from: pack-c5 " + " ".join(wl), file=sys.stderr)
+        print("unknown workload; choose from: pack-c5 pack-c5-ordered " + " ".join(wl), file=sys.stderr)
         sys.exit(2)
     c = wl[args.workload]
     chain = args.workload == "c4"
@@ -350,23 +350,36 @@ def bench_pack(args, torch, hinm, dev):
     ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
     steps = args.steps or 10
     warmup = args.warmup or 2
+    ordered = args.workload == "pack-c5-ordered"
+    sigma = None
+    if ordered:   # a seeded random order of the input channels per tile (stands in for a search result)
+        rng = np.random.default_rng(20496)
+        sigma = torch.from_numpy(np.stack([rng.permutation(c.K) for _ in range(c.T)]).astype(np.int32)).to(dev)
+
+    def pack_once():
+        if ordered:
+            hinm.hinm_pack_ordered(c.M, c.K, c.V, c.Kv, c.dtype, W, sigma, vals, nm, vec, ws, wb)
+        else:
+            hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
     for _ in range(warmup):
-        hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
+        pack_once()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for _ in range(steps):
-        hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
+        pack_once()
     e1.record()
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / steps
     ms = e0.elapsed_time(e1) / steps
     traffic = 2 * c.M * c.K * 2 + vb + nb + cb + 2 * wb   # W read twice, outputs, scores written + read
+    if ordered:
+        traffic += c.T * c.K * 4 + 2 * cb                  # the order read once, the vector index re-read and re-written
     out = {"metric": "hinm_pack_gbps", "value": round(traffic / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
            "steps": steps, "warmup": warmup, "ms_per_step": round(wall * 1e3, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": c.dtype, "data": "synthetic",
-           "config": {"workload": "hinm_pack of " + c.name},
+           "config": {"workload": ("hinm_pack_ordered of " if ordered else "hinm_pack of ") + c.name},
            "roofline": {"bound": "hbm", "achieved": round(traffic / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                         "unit": "GB/s", "frac": round(traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                         "traffic": None, "algorithmic_bytes_per_launch": traffic},

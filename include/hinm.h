@@ -27,8 +27,10 @@
  *                                         p0 < p1 the kept positions (0..3);
  *                                         group g sits in byte g/2, bits
  *                                         4*(g&1) .. 4*(g&1)+3
- *       vec_idx int32          [T][Kv]    surviving columns of tile t, ascending;
- *                                         group g covers entries 4g .. 4g+3
+ *       vec_idx int32          [T][Kv]    surviving columns of tile t, ascending
+ *                                         (hinm_pack) or in a caller-given order
+ *                                         (hinm_pack_ordered); group g covers
+ *                                         entries 4g .. 4g+3
  *   - Channel orders: pi_in is int32[K], row k of (P_in X) is row pi_in[k] of X
  *     (gather); pi_out is int32[M], row r of W_HiNM(P_in X) is written to row
  *     pi_out[r] of Y (scatter).  NULL means identity.  They are not checked
@@ -105,6 +107,19 @@ hinm_status hinm_pack_sizes(const hinm_shape* shape, size_t* vals_bytes, size_t*
 hinm_status hinm_pack(const hinm_shape* shape, const void* W,
                       void* vals, uint8_t* nm_idx, int32_t* vec_idx,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Section 3.2 ("tile-wise input channel permutation"; the per-tile orders sigma_i^t of Section 4.2):
+ * hinm_pack with a caller-given order of the kept column vectors.  tile_order is int32 [T][K] in
+ * device memory, row t a permutation of the input channels 0..K-1; the surviving columns of tile t
+ * (chosen exactly as by hinm_pack) are written to vec_idx in the order in which they appear in
+ * that row instead of ascending, and every four consecutive ones form a 2:4 group.  The product
+ * kernels need nothing else: they follow vec_idx.  tile_order == NULL is hinm_pack.  The rows are
+ * not checked for being permutations: entries outside [0,K) are skipped, and a row that is not a
+ * permutation leaves an unspecified vector index whose entries are surviving columns of the tile.
+ * K above 393216 returns HINM_ERR_UNSUPPORTED.  Workspace as for hinm_pack. */
+hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int32_t* tile_order,
+                              void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* Inverse of hinm_pack: W_out [M][K] = W_HiNM (zeros where pruned).
  * W_out is fully overwritten. */

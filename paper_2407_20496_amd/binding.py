@@ -36,7 +36,7 @@ def library_path() -> str:
 
 def exported_symbols() -> Tuple[str, ...]:
     """Entry points include/hinm.h declares."""
-    return ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_prepare_sizes", "hinm_prepare",
+    return ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_unpack", "hinm_spmm", "hinm_prepare_sizes", "hinm_prepare",
             "hinm_spmm_prepared_workspace", "hinm_spmm_prepared", "hinm_chain_sizes", "hinm_chain",
             "hinm_status_str", "hinm_version")
 
@@ -59,6 +59,8 @@ def load_library():
     szp = C.POINTER(C.c_size_t)
     lib.hinm_pack_sizes.argtypes = [sp, szp, szp, szp, szp]
     lib.hinm_pack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.hinm_pack_ordered.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
     lib.hinm_unpack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.hinm_spmm.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_uint32, C.c_void_p, C.c_size_t,
@@ -72,7 +74,7 @@ def load_library():
     lib.hinm_spmm_prepared_workspace.argtypes = [sp, C.c_int32, szp]
     lib.hinm_spmm_prepared.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                        C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
-    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain",
+    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain",
                  "hinm_prepare_sizes", "hinm_prepare", "hinm_spmm_prepared_workspace", "hinm_spmm_prepared"):
         getattr(lib, name).restype = C.c_int
     lib.hinm_status_str.argtypes = [C.c_int]
@@ -148,6 +150,14 @@ def hinm_pack(M, K, V, Kv, dtype, W, vals, nm_idx, vec_idx, workspace, workspace
     lib = load_library()
     _check(lib.hinm_pack(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(vals), _ptr(nm_idx), _ptr(vec_idx),
                          _ptr(workspace), int(workspace_bytes), _stream(stream)), "hinm_pack")
+
+
+def hinm_pack_ordered(M, K, V, Kv, dtype, W, tile_order, vals, nm_idx, vec_idx, workspace, workspace_bytes,
+                      stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_pack_ordered(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(tile_order), _ptr(vals),
+                                 _ptr(nm_idx), _ptr(vec_idx), _ptr(workspace), int(workspace_bytes),
+                                 _stream(stream)), "hinm_pack_ordered")
 
 
 def hinm_unpack(M, K, V, Kv, dtype, vals, nm_idx, vec_idx, W_out, stream=None) -> None:

@@ -75,8 +75,9 @@ hinm_status hinm_pack_sizes(const hinm_shape* shape, size_t* vals_bytes, size_t*
   return HINM_OK;
 }
 
-hinm_status hinm_pack(const hinm_shape* shape, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
-                      void* workspace, size_t workspace_bytes, void* stream) {
+hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int32_t* tile_order, void* vals,
+                              uint8_t* nm_idx, int32_t* vec_idx, void* workspace, size_t workspace_bytes,
+                              void* stream) {
   hinm_status st = check_shape(shape);
   if (st != HINM_OK) return st;
   if (!W || !vals || !nm_idx || !vec_idx) return HINM_ERR_NULL;
@@ -84,9 +85,15 @@ hinm_status hinm_pack(const hinm_shape* shape, const void* W, void* vals, uint8_
   hinm_pack_sizes(shape, nullptr, nullptr, nullptr, &need);
   if (!workspace || workspace_bytes < need || !aligned(workspace, 8)) return HINM_ERR_WORKSPACE;
   if (!aligned(vals, 8) || !aligned(vec_idx, 4) || !aligned(W, 2)) return HINM_ERR_SHAPE;
-  hipError_t e = launch_pack(*shape, W, vals, nm_idx, vec_idx, static_cast<double*>(workspace),
+  if (tile_order && (!aligned(tile_order, 4) || shape->K > kPackOrderMaxK)) return HINM_ERR_UNSUPPORTED;
+  hipError_t e = launch_pack(*shape, W, tile_order, vals, nm_idx, vec_idx, static_cast<double*>(workspace),
                              static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
+hinm_status hinm_pack(const hinm_shape* shape, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  return hinm_pack_ordered(shape, W, nullptr, vals, nm_idx, vec_idx, workspace, workspace_bytes, stream);
 }
 
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,

@@ -33,8 +33,10 @@ __device__ __forceinline__ uint16_t float_to_bits(float f) {
 // ---- launchers implemented in the kernel translation units -------------------------------------
 // All return hipSuccess or the launch error; all are asynchronous on `stream`.
 
-hipError_t launch_pack(const hinm_shape& s, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
-                       double* scores, hipStream_t stream);
+// tile_order: NULL (kept columns ascending) or int32 [T][K], see hinm_pack_ordered
+hipError_t launch_pack(const hinm_shape& s, const void* W, const int32_t* tile_order, void* vals, uint8_t* nm_idx,
+                       int32_t* vec_idx, double* scores, hipStream_t stream);
+constexpr int kPackOrderMaxK = 32 * 12 * 1024;  // the bitmap of kept columns must fit 48 KB of LDS
 hipError_t launch_unpack(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
                          void* W_out, hipStream_t stream);
 

@@ -271,10 +271,104 @@ __global__ __launch_bounds__(256) void scatter_kernel(const uint16_t* __restrict
   wr[vi[(nib >> 2) & 3u]] = vals[(size_t)r * (Kv / 2) + 2 * g + 1];
 }
 
+// The same emission with the row of W staged in LDS: one workgroup per row reads the row once, fully
+// coalesced, and picks the kept columns from LDS.  The picks of emit_kernel go to global memory,
+// which costs one address-unit cycle per lane and is slow as soon as the vector index is not
+// ascending (a caller-given tile order).  Needs 2 K bytes of LDS.
+constexpr int kEmitRowMaxK = 32 * 1024;
+
+__global__ __launch_bounds__(kEmitThreads) void emit_rows_kernel(const uint16_t* __restrict__ W,
+                                                                 const int32_t* __restrict__ vec_idx,
+                                                                 uint16_t* __restrict__ vals,
+                                                                 uint8_t* __restrict__ nm_idx, int K, int V, int Kv,
+                                                                 bool vec8) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t row[];  // K elements
+  const int r = blockIdx.x;
+  const int t = r / V;
+  const uint16_t* wr = W + (size_t)r * K;
+  if (vec8) {  // K % 8 == 0 and W 16-byte aligned
+    for (int i = threadIdx.x; i < K / 8; i += kEmitThreads)
+      reinterpret_cast<uint4*>(row)[i] = reinterpret_cast<const uint4*>(wr)[i];
+  } else {
+    for (int i = threadIdx.x; i < K; i += kEmitThreads) row[i] = wr[i];
+  }
+  __syncthreads();
+  const int bytes_per_row = Kv / 8;
+  for (int b = threadIdx.x; b < bytes_per_row; b += kEmitThreads) {
+    const int32_t* vi = vec_idx + (size_t)t * Kv + 8 * b;
+    uint16_t out[4];
+    uint32_t byte = 0;
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      uint16_t w[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) w[q] = row[vi[4 * g + q]];
+      uint32_t p0, p1;
+      top2_of_4(w, p0, p1);
+      out[2 * g] = w[p0];
+      out[2 * g + 1] = w[p1];
+      byte |= (p0 | (p1 << 2)) << (4 * g);
+    }
+    uint2 packed;
+    packed.x = (uint32_t)out[0] | ((uint32_t)out[1] << 16);
+    packed.y = (uint32_t)out[2] | ((uint32_t)out[3] << 16);
+    *reinterpret_cast<uint2*>(vals + (size_t)r * (Kv / 2) + 4 * b) = packed;
+    nm_idx[(size_t)r * bytes_per_row + b] = (uint8_t)byte;
+  }
+}
+
+// Tile-wise input-channel order (Section 3.2, "tile-wise input channel permutation"): the kept
+// columns of tile t, so far ascending, are rewritten in the order in which they appear in
+// sigma[t][0..K), a permutation of the input channels.  One workgroup per tile, in place: a bitmap of
+// the kept columns is built in LDS first, then sigma is swept in order with workgroup prefix sums.
+// Entries of sigma outside [0, K) are skipped and nothing is written past slot Kv - 1, so a sigma that
+// is not a permutation leaves an unspecified but in-range vector index.
+constexpr int kOrderThreads = 1024;
+
+__global__ __launch_bounds__(kOrderThreads) void order_kernel(const int32_t* __restrict__ sigma,
+                                                              int32_t* __restrict__ vec_idx, int K, int Kv) {
+  extern __shared__ uint32_t kept_bits[];  // ceil(K / 32) words
+  __shared__ uint32_t wave_count[kOrderThreads / 64];
+  const int t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  int32_t* vi = vec_idx + (size_t)t * Kv;
+  const int32_t* sg = sigma + (size_t)t * K;
+  for (int w = tid; w < (K + 31) / 32; w += kOrderThreads) kept_bits[w] = 0;
+  __syncthreads();
+  for (int j = tid; j < Kv; j += kOrderThreads) {
+    const int c = vi[j];
+    atomicOr(&kept_bits[c >> 5], 1u << (c & 31));
+  }
+  __syncthreads();
+  int done = 0;  // kept columns written so far (same value in every thread)
+  for (int base = 0; base < K; base += kOrderThreads) {
+    const int i = base + tid;
+    const int c = (i < K) ? sg[i] : -1;
+    const bool take = c >= 0 && c < K && ((kept_bits[c >> 5] >> (c & 31)) & 1u);
+    const uint64_t votes = __ballot(take);
+    const int before_in_wave = __popcll(votes & ((1ull << lane) - 1));
+    if (lane == 0) wave_count[wave] = (uint32_t)__popcll(votes);
+    __syncthreads();
+    int before_waves = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kOrderThreads / 64; ++w) {
+      const int n = (int)wave_count[w];
+      if (w < wave) before_waves += n;
+      total += n;
+    }
+    const int pos = done + before_waves + before_in_wave;
+    if (take && pos < Kv) vi[pos] = c;
+    done += total;
+    __syncthreads();  // wave_count is rewritten by the next sweep
+  }
+}
+
 }  // namespace
 
-hipError_t launch_pack(const hinm_shape& s, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
-                       double* scores, hipStream_t stream) {
+hipError_t launch_pack(const hinm_shape& s, const void* W, const int32_t* tile_order, void* vals, uint8_t* nm_idx,
+                       int32_t* vec_idx, double* scores, hipStream_t stream) {
   const int T = s.M / s.V;
   const uint16_t* Wb = static_cast<const uint16_t*>(W);
   const bool vec8 = (s.K % 8 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15u) == 0);
@@ -295,6 +389,17 @@ hipError_t launch_pack(const hinm_shape& s, const void* W, void* vals, uint8_t* 
   else select_kernel<0><<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (tile_order) {
+    order_kernel<<<T, kOrderThreads, (size_t)((s.K + 31) / 32) * 4, stream>>>(tile_order, vec_idx, s.K, s.Kv);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  // rows long enough to fill a workgroup go through LDS; short rows keep the flat kernel
+  if (s.K <= kEmitRowMaxK && s.Kv >= 8 * kEmitThreads) {
+    emit_rows_kernel<<<(unsigned)s.M, kEmitThreads, (size_t)((s.K + 7) / 8 * 8) * 2, stream>>>(
+        Wb, vec_idx, static_cast<uint16_t*>(vals), nm_idx, s.K, s.V, s.Kv, vec8);
+    return hipGetLastError();
+  }
   const int64_t emit_threads = (int64_t)s.M * (s.Kv / 8);
   emit_kernel<<<(unsigned)((emit_threads + kEmitThreads - 1) / kEmitThreads), kEmitThreads, 0, stream>>>(
       Wb, vec_idx, static_cast<uint16_t*>(vals), nm_idx, s.M, s.K, s.V, s.Kv);

@@ -35,7 +35,8 @@ class Packed:
                 self.vec_idx.cpu().numpy().reshape(self.M // self.V, self.Kv))
 
 
-def gpu_pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, W_dev=None) -> Packed:
+def gpu_pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, W_dev=None, sigma=None) -> Packed:
+    """hinm_pack, or hinm_pack_ordered when sigma (int [T, K], per-tile channel order) is given."""
     M, K = W_bits.shape
     vb, nb, cb, wb = hinm.hinm_pack_sizes(M, K, V, Kv, dtype)
     Wd = dev_bits(W_bits) if W_dev is None else W_dev
@@ -43,7 +44,10 @@ def gpu_pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, W_dev=None) -> Pac
     nm = torch.empty(nb, dtype=torch.uint8, device=DEV)
     vec = torch.empty(cb // 4, dtype=torch.int32, device=DEV)
     ws = torch.empty(wb // 8, dtype=torch.float64, device=DEV)
-    hinm.hinm_pack(M, K, V, Kv, dtype, Wd, vals, nm, vec, ws, wb)
+    if sigma is None:
+        hinm.hinm_pack(M, K, V, Kv, dtype, Wd, vals, nm, vec, ws, wb)
+    else:
+        hinm.hinm_pack_ordered(M, K, V, Kv, dtype, Wd, dev_i32(sigma), vals, nm, vec, ws, wb)
     torch.cuda.synchronize()
     return Packed(M, K, V, Kv, dtype, vals, nm, vec)
 

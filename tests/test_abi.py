@@ -61,6 +61,12 @@ def test_null_and_workspace_errors_are_reported_before_any_launch():
     assert lib.hinm_pack(C.byref(sh), fake, fake, fake, fake, None, 0, None) == 4
     assert lib.hinm_pack(C.byref(sh), fake, fake, fake, fake, fake, 16, None) == 4      # too small
     assert lib.hinm_unpack(C.byref(sh), fake, fake, None, fake, None) == 1
+    # ordered pack: same checks as hinm_pack, then the order's alignment and the K limit of its bitmap
+    assert lib.hinm_pack_ordered(C.byref(sh), None, fake, fake, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.hinm_pack_ordered(C.byref(sh), fake, fake, fake, fake, fake, None, 0, None) == 4
+    assert lib.hinm_pack_ordered(C.byref(sh), fake, fake + 2, fake, fake, fake, fake, 1 << 20, None) == 5
+    big = binding._Shape(16, 400000, 16, 8, 0)
+    assert lib.hinm_pack_ordered(C.byref(big), fake, fake, fake, fake, fake, fake, 1 << 30, None) == 5
     # spmm: null X, bad N, bad ld, misaligned X, unknown flag, two kernels forced
     args = dict(N=64, vals=fake, nm=fake, vec=fake, X=fake, ldx=64, Y=fake, ldy=64, flags=0)
 
