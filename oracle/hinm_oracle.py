@@ -23,6 +23,12 @@ What it follows (arXiv 2407.20496):
     kept column vectors of a tile may be arranged in a caller-given order before
     the 2:4 step (tile_order, pack's sigma argument); the search that finds a
     good order is not part of this file.
+  * Section 4.1 (Eq. 1-3) and Section 5.1: both masks maximise a retained
+    saliency rho that need not come from the weights themselves (magnitude or
+    second-order scores); pack's rho argument takes such a score per weight.
+  * Section 5.1.2: during gradual pruning a layer first carries the column-vector
+    mask alone and receives the 2:4 mask later; pack_vectors / unpack_vectors
+    hold that intermediate state (all Kv surviving entries of every row).
 
 Readings where the paper is silent (all repeated in the design notes):
   saliency of a V x 1 vector = sum of squares (L2), accumulated in binary64 in
@@ -33,13 +39,20 @@ Readings where the paper is silent (all repeated in the design notes):
   pi_in[k] of X) and P_out scatters (row r of the product lands in row
   pi_out[r] of Y); the product is accumulated in float32 unless float64 is
   requested, and rounded to the storage type with round-to-nearest-even.
+  With a caller-given rho (float32, one score per weight, no NaN): the saliency
+  of a vector is the plain sum of its V scores, accumulated in binary64 in
+  ascending row order starting from +0; larger sum wins, equal sums -> lower
+  column; inside a group of four the two largest scores are kept, equal scores
+  -> lower position (-0 and +0 are equal); the stored values are always W's.
 
 16-bit tensors are uint16 bit patterns plus a dtype tag, "f16" or "bf16".
 
 Pins: tests/test_oracle_*.py (brute-force enumeration of Eq. 2 / Eq. 3 on tiny
 inputs, exact kept counts, the sparsity formula, pack/unpack round trip,
 identity-permutation and dense-library reductions, the hand-derived examples in
-tests/golden/, one of them with a tile-wise order).  The paper prints no numeric worked example for this path.
+tests/golden/, one with a tile-wise order and one with caller-given scores; for
+rho also the reductions rho = w^2 and V = 1, and for the vector-only state its
+2:4 completion).  The paper prints no numeric worked example for this path.
 """
 from __future__ import annotations
 
@@ -101,10 +114,26 @@ def vector_scores(W_bits: np.ndarray, dtype: str, V: int) -> np.ndarray:
     return s
 
 
-def vector_index(W_bits: np.ndarray, dtype: str, V: int, Kv: int) -> np.ndarray:
+def vector_scores_rho(rho: np.ndarray, V: int) -> np.ndarray:
+    """score[t, k] = sum_{i<V} rho[tV+i, k] for caller-given per-weight saliency
+    (Section 4.1, the rho of Eq. 1-3; Section 5.1 names magnitude and second-order
+    scores): float32 inputs, binary64 sum from +0, rows added in ascending order."""
+    rho = np.asarray(rho)
+    assert rho.dtype == np.float32 and not np.isnan(rho).any()
+    M, K = rho.shape
+    assert M % V == 0
+    Rt = rho.astype(np.float64).reshape(M // V, V, K)
+    s = np.zeros((M // V, K), dtype=np.float64)
+    for i in range(V):  # sequential on purpose: pins the rounding order
+        s = s + Rt[:, i, :]
+    return s
+
+
+def vector_index(W_bits: np.ndarray, dtype: str, V: int, Kv: int, rho: Optional[np.ndarray] = None) -> np.ndarray:
     """Per tile, the Kv columns of largest score (ties: lower column first),
-    returned in ascending column order: int32 [T, Kv]."""
-    s = vector_scores(W_bits, dtype, V)
+    returned in ascending column order: int32 [T, Kv].  The score is the L2
+    saliency of W's vectors, or the summed caller-given rho."""
+    s = vector_scores(W_bits, dtype, V) if rho is None else vector_scores_rho(rho, V)
     T, K = s.shape
     assert 0 < Kv <= K
     cols = np.arange(K)
@@ -148,22 +177,35 @@ def nm_positions(C: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     return kept[..., 0], kept[..., 1]
 
 
-def pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, sigma: Optional[np.ndarray] = None):
+def nm_positions_signed(R: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """R: float64 [..., G, 4] of caller-given scores.  Kept positions p0 < p1: the two
+    largest scores as signed numbers, ties (including -0 against +0) -> lower position."""
+    order = np.argsort(-(R + 0.0), axis=-1, kind="stable")  # adding +0 turns -0 into +0
+    kept = np.sort(order[..., :2], axis=-1)
+    return kept[..., 0], kept[..., 1]
+
+
+def pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, sigma: Optional[np.ndarray] = None,
+         rho: Optional[np.ndarray] = None):
     """Dense W (uint16 bits [M, K]) -> (vals uint16 [M, Kv/2], nm_idx uint8
     [M, Kv/8], vec_idx int32 [T, Kv]).  sigma (int [T, K], optional): per-tile order of the
-    input channels, see tile_order."""
+    input channels, see tile_order.  rho (float32 [M, K], optional): per-weight saliency that
+    replaces W's own magnitudes in both selections (Section 4.1); the stored values stay W's."""
     W_bits = np.ascontiguousarray(W_bits, dtype=np.uint16)
     M, K = W_bits.shape
     assert M % V == 0 and Kv % 8 == 0 and 0 < Kv <= K
     T = M // V
-    vec_idx = tile_order(vector_index(W_bits, dtype, V, Kv), sigma, K)
+    vec_idx = tile_order(vector_index(W_bits, dtype, V, Kv, rho), sigma, K)
     G = Kv // 4
     vals = np.empty((M, Kv // 2), dtype=np.uint16)
     nm_idx = np.empty((M, Kv // 8), dtype=np.uint8)
     for t in range(T):
         Cb = W_bits[t * V:(t + 1) * V][:, vec_idx[t]]            # compressed tile, bits, [V, Kv]
-        C = decode(Cb, dtype).reshape(V, G, 4)
-        p0, p1 = nm_positions(C)                                  # [V, G] each
+        if rho is None:
+            p0, p1 = nm_positions(decode(Cb, dtype).reshape(V, G, 4))     # saliency of an entry: its magnitude
+        else:
+            R = np.asarray(rho)[t * V:(t + 1) * V][:, vec_idx[t]].astype(np.float64)
+            p0, p1 = nm_positions_signed(R.reshape(V, G, 4))
         Cb4 = Cb.reshape(V, G, 4)
         v0 = np.take_along_axis(Cb4, p0[..., None], axis=-1)[..., 0]
         v1 = np.take_along_axis(Cb4, p1[..., None], axis=-1)[..., 0]
@@ -174,6 +216,33 @@ def pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, sigma: Optional[np.nda
         nib = (p0 | (p1 << 2)).astype(np.uint8)                   # [V, G]
         nm_idx[t * V:(t + 1) * V] = nib[:, 0::2] | (nib[:, 1::2] << 4)
     return vals, nm_idx, vec_idx
+
+
+def pack_vectors(W_bits: np.ndarray, dtype: str, V: int, Kv: int, sigma: Optional[np.ndarray] = None,
+                 rho: Optional[np.ndarray] = None):
+    """The layer after column-vector pruning alone (Section 3.1, first step; Section 5.1.2, the
+    state a layer is in until the target vector sparsity is reached): (vals_v uint16 [M, Kv],
+    vec_idx int32 [T, Kv]) with vals_v[r, j] = W[r, vec_idx[r // V, j]]."""
+    W_bits = np.ascontiguousarray(W_bits, dtype=np.uint16)
+    M, K = W_bits.shape
+    assert M % V == 0 and 0 < Kv <= K
+    T = M // V
+    vec_idx = tile_order(vector_index(W_bits, dtype, V, Kv, rho), sigma, K)
+    vals_v = np.empty((M, Kv), dtype=np.uint16)
+    for t in range(T):
+        vals_v[t * V:(t + 1) * V] = W_bits[t * V:(t + 1) * V][:, vec_idx[t]]
+    return vals_v, vec_idx
+
+
+def unpack_vectors(vals_v: np.ndarray, vec_idx: np.ndarray, M: int, K: int, V: int) -> np.ndarray:
+    """Inverse of pack_vectors into an all-zero matrix: uint16 bits [M, K] of M_v (.) W."""
+    T, Kv = vec_idx.shape
+    assert T * V == M
+    W = np.zeros((M, K), dtype=np.uint16)
+    for r in range(M):
+        for j in range(Kv):
+            W[r, vec_idx[r // V, j]] = vals_v[r, j]
+    return W
 
 
 def unpack(vals: np.ndarray, nm_idx: np.ndarray, vec_idx: np.ndarray, M: int, K: int, V: int) -> np.ndarray:
