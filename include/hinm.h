@@ -121,6 +121,30 @@ hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int3
                               void* vals, uint8_t* nm_idx, int32_t* vec_idx,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 4.1 (the saliency rho of Eq. 1-3; Section 5.1 names magnitude and second-order scores):
+ * hinm_pack with caller-given scores.  rho is float32 [M][K] in device memory, one score per
+ * weight, free of NaN.  Vector saliency = the sum of the V scores of the vector, accumulated in
+ * IEEE binary64 in ascending row order starting from +0; the Kv largest sums survive (signed
+ * comparison), equal sums -> lower column.  Inside every group of four surviving entries the two
+ * largest scores are kept (signed comparison, -0 equals +0), equal -> lower position.  vals holds
+ * bit copies of W at the kept places, as in hinm_pack.  tile_order as in hinm_pack_ordered, or
+ * NULL.  Workspace as for hinm_pack. */
+hinm_status hinm_pack_scored(const hinm_shape* shape, const void* W, const float* rho,
+                             const int32_t* tile_order,
+                             void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Section 3.1 (first step) / Section 5.1.2 (gradual pruning keeps a layer in this state until the
+ * target vector sparsity is reached): column-vector pruning alone, no 2:4 step.  vals_v is
+ * 16-bit [M][Kv] in device memory, 16-byte aligned: vals_v[r][j] = W[r][vec_idx[r / V][j]], a
+ * bit copy; vec_idx as written by hinm_pack.  rho (as in hinm_pack_scored) and tile_order (as in
+ * hinm_pack_ordered) may each be NULL.  Applying 2:4 to every four consecutive entries of a row of
+ * vals_v gives what hinm_pack stores.  Workspace as for hinm_pack. */
+hinm_status hinm_pack_vectors(const hinm_shape* shape, const void* W, const float* rho,
+                              const int32_t* tile_order,
+                              void* vals_v, int32_t* vec_idx,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* Inverse of hinm_pack: W_out [M][K] = W_HiNM (zeros where pruned).
  * W_out is fully overwritten. */
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx,
@@ -136,6 +160,20 @@ hinm_status hinm_spmm(const hinm_shape* shape, int32_t N,
                       const int32_t* pi_in, const int32_t* pi_out,
                       const void* X, int64_t ldx, void* Y, int64_t ldy,
                       uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Section 5.1.2 (a layer of a gradually pruned model before its 2:4 step) with the channel orders
+ * of Section 3.2 / Section 5.3:
+ *     Y[pi_out[r]][n] = sum_j vals_v[r][j] * X[pi_in[vec_idx[r / V][j]]][n],
+ * vals_v and vec_idx as written by hinm_pack_vectors (vals_v 16-byte aligned).  fp32 accumulation,
+ * rounding, pi_in / pi_out, ldx / ldy and alignment rules as for hinm_spmm.  flags: HINM_EPI_RELU,
+ * HINM_OUT_F32, HINM_KERNEL_REFERENCE (one thread per output element); anything else returns
+ * HINM_ERR_UNSUPPORTED.  V in {32, 64, 96, 128} runs on the dense MFMA, other shapes on the
+ * plain kernel.  Needs no workspace. */
+hinm_status hinm_spmm_vectors(const hinm_shape* shape, int32_t N,
+                              const void* vals_v, const int32_t* vec_idx,
+                              const int32_t* pi_in, const int32_t* pi_out,
+                              const void* X, int64_t ldx, void* Y, int64_t ldy,
+                              uint32_t flags, void* stream);
 
 /* ---- device-tuned form -----------------------------------------------------------------------
  * Section 3.2 settles every layer's channel orders offline and rewrites the vector indices

@@ -36,7 +36,8 @@ def library_path() -> str:
 
 def exported_symbols() -> Tuple[str, ...]:
     """Entry points include/hinm.h declares."""
-    return ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_unpack", "hinm_spmm", "hinm_prepare_sizes", "hinm_prepare",
+    return ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_pack_scored", "hinm_pack_vectors",
+            "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_prepare_sizes", "hinm_prepare",
             "hinm_spmm_prepared_workspace", "hinm_spmm_prepared", "hinm_chain_sizes", "hinm_chain",
             "hinm_status_str", "hinm_version")
 
@@ -61,6 +62,12 @@ def load_library():
     lib.hinm_pack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.hinm_pack_ordered.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
+    lib.hinm_pack_scored.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.hinm_pack_vectors.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
+    lib.hinm_spmm_vectors.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_int64, C.c_void_p, C.c_int64, C.c_uint32, C.c_void_p]
     lib.hinm_unpack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.hinm_spmm.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_uint32, C.c_void_p, C.c_size_t,
@@ -74,7 +81,8 @@ def load_library():
     lib.hinm_spmm_prepared_workspace.argtypes = [sp, C.c_int32, szp]
     lib.hinm_spmm_prepared.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                        C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
-    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_unpack", "hinm_spmm", "hinm_chain_sizes", "hinm_chain",
+    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_pack_scored", "hinm_pack_vectors",
+                 "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_chain_sizes", "hinm_chain",
                  "hinm_prepare_sizes", "hinm_prepare", "hinm_spmm_prepared_workspace", "hinm_spmm_prepared"):
         getattr(lib, name).restype = C.c_int
     lib.hinm_status_str.argtypes = [C.c_int]
@@ -158,6 +166,30 @@ def hinm_pack_ordered(M, K, V, Kv, dtype, W, tile_order, vals, nm_idx, vec_idx, 
     _check(lib.hinm_pack_ordered(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(tile_order), _ptr(vals),
                                  _ptr(nm_idx), _ptr(vec_idx), _ptr(workspace), int(workspace_bytes),
                                  _stream(stream)), "hinm_pack_ordered")
+
+
+def hinm_pack_scored(M, K, V, Kv, dtype, W, rho, tile_order, vals, nm_idx, vec_idx, workspace, workspace_bytes,
+                     stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_pack_scored(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(rho), _ptr(tile_order), _ptr(vals),
+                                _ptr(nm_idx), _ptr(vec_idx), _ptr(workspace), int(workspace_bytes),
+                                _stream(stream)), "hinm_pack_scored")
+
+
+def hinm_pack_vectors(M, K, V, Kv, dtype, W, rho, tile_order, vals_v, vec_idx, workspace, workspace_bytes,
+                      stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_pack_vectors(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(rho), _ptr(tile_order),
+                                 _ptr(vals_v), _ptr(vec_idx), _ptr(workspace), int(workspace_bytes),
+                                 _stream(stream)), "hinm_pack_vectors")
+
+
+def hinm_spmm_vectors(M, K, V, Kv, dtype, N, vals_v, vec_idx, pi_in, pi_out, X, ldx, Y, ldy, flags=0,
+                      stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_spmm_vectors(C.byref(_shape(M, K, V, Kv, dtype)), int(N), _ptr(vals_v), _ptr(vec_idx),
+                                 _ptr(pi_in), _ptr(pi_out), _ptr(X), int(ldx), _ptr(Y), int(ldy), int(flags),
+                                 _stream(stream)), "hinm_spmm_vectors")
 
 
 def hinm_unpack(M, K, V, Kv, dtype, vals, nm_idx, vec_idx, W_out, stream=None) -> None:

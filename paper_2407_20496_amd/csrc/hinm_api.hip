@@ -75,25 +75,46 @@ hinm_status hinm_pack_sizes(const hinm_shape* shape, size_t* vals_bytes, size_t*
   return HINM_OK;
 }
 
-hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int32_t* tile_order, void* vals,
-                              uint8_t* nm_idx, int32_t* vec_idx, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+static hinm_status run_pack(const hinm_shape* shape, const void* W, const float* rho, bool with_rho,
+                            const int32_t* tile_order, void* vals, uint8_t* nm_idx, bool with_nm, int32_t* vec_idx,
+                            void* workspace, size_t workspace_bytes, void* stream) {
   hinm_status st = check_shape(shape);
   if (st != HINM_OK) return st;
-  if (!W || !vals || !nm_idx || !vec_idx) return HINM_ERR_NULL;
+  if (!W || !vals || !vec_idx || (with_nm && !nm_idx) || (with_rho && !rho)) return HINM_ERR_NULL;
   size_t need = 0;
   hinm_pack_sizes(shape, nullptr, nullptr, nullptr, &need);
   if (!workspace || workspace_bytes < need || !aligned(workspace, 8)) return HINM_ERR_WORKSPACE;
-  if (!aligned(vals, 8) || !aligned(vec_idx, 4) || !aligned(W, 2)) return HINM_ERR_SHAPE;
+  if (!aligned(vals, with_nm ? 8 : 16) || !aligned(vec_idx, 4) || !aligned(W, 2)) return HINM_ERR_SHAPE;
+  if (with_rho && !aligned(rho, 4)) return HINM_ERR_SHAPE;
   if (tile_order && (!aligned(tile_order, 4) || shape->K > kPackOrderMaxK)) return HINM_ERR_UNSUPPORTED;
-  hipError_t e = launch_pack(*shape, W, tile_order, vals, nm_idx, vec_idx, static_cast<double*>(workspace),
-                             static_cast<hipStream_t>(stream));
+  const PackArgs a{*shape, W, rho, tile_order, vals, with_nm ? nm_idx : nullptr, vec_idx,
+                   static_cast<double*>(workspace)};
+  hipError_t e = launch_pack(a, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 
 hinm_status hinm_pack(const hinm_shape* shape, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
                       void* workspace, size_t workspace_bytes, void* stream) {
-  return hinm_pack_ordered(shape, W, nullptr, vals, nm_idx, vec_idx, workspace, workspace_bytes, stream);
+  return run_pack(shape, W, nullptr, false, nullptr, vals, nm_idx, true, vec_idx, workspace, workspace_bytes, stream);
+}
+
+hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int32_t* tile_order, void* vals,
+                              uint8_t* nm_idx, int32_t* vec_idx, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  return run_pack(shape, W, nullptr, false, tile_order, vals, nm_idx, true, vec_idx, workspace, workspace_bytes,
+                  stream);
+}
+
+hinm_status hinm_pack_scored(const hinm_shape* shape, const void* W, const float* rho, const int32_t* tile_order,
+                             void* vals, uint8_t* nm_idx, int32_t* vec_idx, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  return run_pack(shape, W, rho, true, tile_order, vals, nm_idx, true, vec_idx, workspace, workspace_bytes, stream);
+}
+
+hinm_status hinm_pack_vectors(const hinm_shape* shape, const void* W, const float* rho, const int32_t* tile_order,
+                              void* vals_v, int32_t* vec_idx, void* workspace, size_t workspace_bytes, void* stream) {
+  return run_pack(shape, W, rho, rho != nullptr, tile_order, vals_v, nullptr, false, vec_idx, workspace,
+                  workspace_bytes, stream);
 }
 
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
@@ -115,6 +136,26 @@ hinm_status hinm_spmm(const hinm_shape* shape, int32_t N, const void* vals, cons
   SpmmArgs a{*shape, N, vals, nm_idx, vec_idx, pi_in, pi_out, X, ldx, Y, ldy,
              (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0};
   return run_spmm(a, flags, static_cast<hipStream_t>(stream));
+}
+
+hinm_status hinm_spmm_vectors(const hinm_shape* shape, int32_t N, const void* vals_v, const int32_t* vec_idx,
+                              const int32_t* pi_in, const int32_t* pi_out, const void* X, int64_t ldx, void* Y,
+                              int64_t ldy, uint32_t flags, void* stream) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (!vals_v || !vec_idx || !X || !Y) return HINM_ERR_NULL;
+  if (N <= 0 || ldx < N || ldy < N) return HINM_ERR_SHAPE;
+  if (N > 1 && (ldx % 8 != 0 || ldy % 8 != 0)) return HINM_ERR_SHAPE;
+  if (!aligned(vals_v, 16) || !aligned(X, 16) || !aligned(Y, 16)) return HINM_ERR_SHAPE;
+  if (flags & ~(uint32_t)(HINM_EPI_RELU | HINM_OUT_F32 | HINM_KERNEL_REFERENCE)) return HINM_ERR_UNSUPPORTED;
+  const VectorsArgs a{*shape, N, vals_v, vec_idx, pi_in, pi_out, X, ldx, Y, ldy,
+                      (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0};
+  hipError_t e;
+  if (!(flags & HINM_KERNEL_REFERENCE) && spmm_vectors_mfma_supported(a))
+    e = launch_spmm_vectors_mfma(a, static_cast<hipStream_t>(stream));
+  else
+    e = launch_spmm_vectors_plain(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 
 static hinm_status check_prepared_call(const hinm_shape* shape, int32_t N, const void* prepared, const void* X,

@@ -33,9 +33,17 @@ __device__ __forceinline__ uint16_t float_to_bits(float f) {
 // ---- launchers implemented in the kernel translation units -------------------------------------
 // All return hipSuccess or the launch error; all are asynchronous on `stream`.
 
-// tile_order: NULL (kept columns ascending) or int32 [T][K], see hinm_pack_ordered
-hipError_t launch_pack(const hinm_shape& s, const void* W, const int32_t* tile_order, void* vals, uint8_t* nm_idx,
-                       int32_t* vec_idx, double* scores, hipStream_t stream);
+struct PackArgs {
+  hinm_shape s;
+  const void* W;
+  const float* rho;           // NULL: the weights' own squares / magnitudes; else float32 [M][K] scores
+  const int32_t* tile_order;  // NULL: kept columns ascending; else int32 [T][K], see hinm_pack_ordered
+  void* vals;                 // [M][Kv/2] after 2:4, or [M][Kv] when nm_idx is NULL
+  uint8_t* nm_idx;            // NULL: column-vector pruning only, no 2:4 step
+  int32_t* vec_idx;
+  double* scores;             // workspace, [T][K]
+};
+hipError_t launch_pack(const PackArgs& a, hipStream_t stream);
 constexpr int kPackOrderMaxK = 32 * 12 * 1024;  // the bitmap of kept columns must fit 48 KB of LDS
 hipError_t launch_unpack(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
                          void* W_out, hipStream_t stream);
@@ -65,6 +73,25 @@ hipError_t launch_spmm_tile(const SpmmArgs& a, hipStream_t stream);
 bool spmm_skinny_supported(const SpmmArgs& a);
 hipError_t launch_spmm_skinny(const SpmmArgs& a, hipStream_t stream);
 
+// ---- layer with the column-vector mask alone (all Kv surviving entries of a row stored) ---------
+struct VectorsArgs {
+  hinm_shape s;
+  int32_t N;
+  const void* vals_v;  // [M][Kv]
+  const int32_t* vec_idx;
+  const int32_t* pi_in;
+  const int32_t* pi_out;
+  const void* X;
+  int64_t ldx;
+  void* Y;
+  int64_t ldy;
+  bool relu;
+  bool out_f32;
+};
+// Dense-MFMA tile kernel: V in {32, 64, 96, 128}, ldx % 8 == 0, ldy % 8 == 0.
+bool spmm_vectors_mfma_supported(const VectorsArgs& a);
+hipError_t launch_spmm_vectors_mfma(const VectorsArgs& a, hipStream_t stream);
+hipError_t launch_spmm_vectors_plain(const VectorsArgs& a, hipStream_t stream);
 
 // ---- device-tuned ("prepared") layer form -------------------------------------------------------------
 hipError_t launch_prepare(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,

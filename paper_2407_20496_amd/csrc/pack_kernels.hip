@@ -8,6 +8,12 @@
 //   emit   : per row and group of four surviving columns, the two largest magnitudes (equal:
 //            lower position first) -> packed values + NM nibble
 // plus the inverse (unpack) used by the round-trip checks.
+//
+// Variants of the same passes: per-weight saliency scores rho given by the caller (Section 4.1, the
+// rho of Eq. 1-3) replace the squares in `score` and the magnitudes in `emit`; a caller-given
+// tile-wise order of the kept columns (Section 3.2) adds an `order` pass after `select`; and the
+// vector-only state of gradual pruning (Section 5.1.2) replaces `emit` by a plain gather of the
+// surviving columns.
 #include "hinm_internal.h"
 
 namespace hinm {
@@ -55,12 +61,48 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const uint16_t* __
   for (int e = 0; e < VEC; ++e) out[e] = s[e];
 }
 
+// The same walk over caller-given scores: s[t][k] = sum_i rho[tV+i][k], binary64, ascending rows,
+// starting from +0 (so a sum is never -0).
+template <int VEC>
+__global__ __launch_bounds__(kScoreThreads) void score_rho_kernel(const float* __restrict__ rho,
+                                                                  double* __restrict__ scores, int K, int V) {
+  const int t = blockIdx.y;
+  const int64_t c0 = ((int64_t)blockIdx.x * kScoreThreads + threadIdx.x) * VEC;
+  if (c0 >= K) return;
+  const float* p = rho + (size_t)t * V * K + c0;
+  double s[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) s[e] = 0.0;
+  for (int i = 0; i < V; ++i) {
+    float w[VEC];
+    if constexpr (VEC == 4) {
+      const float4 q = *reinterpret_cast<const float4*>(p);
+      w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) w[e] = p[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s[e] += (double)w[e];
+    p += K;
+  }
+  double* out = scores + (size_t)t * K + c0;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) out[e] = s[e];
+}
+
 // ---------------------------------------------------------------------------------------------
-// select: one workgroup per tile.  Scores are non-negative doubles, so their bit patterns order
-// like unsigned 64-bit integers.  An 8-bit-digit radix descent finds the Kv-th largest key tau and
+// select: one workgroup per tile.  A score's bit pattern is turned into a key that orders like an
+// unsigned 64-bit integer (sign bit set for non-negative values, all bits flipped for negative ones;
+// sums start from +0, so -0 does not occur and equal values have equal keys; NaN is not supported).
+// An 8-bit-digit radix descent finds the Kv-th largest key tau and
 // how many keys equal to tau still have to be taken; those are taken from the lowest columns.
 // A final in-order sweep with workgroup prefix sums writes the kept columns ascending.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long ordered_key(unsigned long long bits) {
+  return (bits >> 63) ? ~bits : (bits | (1ull << 63));
+}
+
 __device__ __forceinline__ uint32_t block_exclusive_count(bool flag, uint32_t* wave_tot, uint32_t& total) {
   const unsigned long long bal = __ballot(flag);
   const int lane = threadIdx.x & 63;
@@ -96,7 +138,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
 #pragma unroll
     for (int c = 0; c < KPT; ++c) {
       const int k = c * kSelectThreads + threadIdx.x;
-      held[c] = (k < K) ? key[k] : 0ull;
+      held[c] = (k < K) ? ordered_key(key[k]) : 0ull;
     }
   }
   const int chunks = KPT > 0 ? KPT : (K + kSelectThreads - 1) / kSelectThreads;
@@ -111,7 +153,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
       const int k = c * kSelectThreads + threadIdx.x;
       unsigned long long u;
       if constexpr (KPT > 0) u = held[c];
-      else u = (k < K) ? key[k] : 0ull;
+      else u = (k < K) ? ordered_key(key[k]) : 0ull;
       bool pending = (k < K) && ((u & mask) == prefix);
       const uint32_t d = (uint32_t)(u >> shift) & 255u;
       // Scores of one tile share their leading bits, so in the first passes nearly every lane hits the
@@ -179,7 +221,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
     const bool in = k < K;
     unsigned long long u;
     if constexpr (KPT > 0) u = held[c];
-    else u = in ? key[k] : 0ull;
+    else u = in ? ordered_key(key[k]) : 0ull;
     const bool gt = in && u > tau;
     const bool eq = in && u == tau;
     uint32_t eq_total, kept_total;
@@ -214,7 +256,58 @@ __device__ __forceinline__ void top2_of_4(const uint16_t w[4], uint32_t& p0, uin
   p1 = 31 - __builtin_clz(kept_mask);
 }
 
+// The same choice on caller-given scores, compared as signed numbers (-0 equals +0).
+__device__ __forceinline__ void top2_of_4_scores(const float sc[4], uint32_t& p0, uint32_t& p1) {
+  uint32_t kept_mask = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    uint32_t rank = 0;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+      if (o == q) continue;
+      rank += (sc[o] > sc[q] || (sc[o] == sc[q] && o < q)) ? 1u : 0u;
+    }
+    if (rank < 2) kept_mask |= 1u << q;
+  }
+  p0 = __builtin_ctz(kept_mask);
+  p1 = 31 - __builtin_clz(kept_mask);
+}
+
+// One NM byte = two groups of four surviving columns of one row: picks the eight entries through
+// `w_at` (and their scores through `rho_at` when SCORED), stores four values and the byte.
+template <bool SCORED, typename WAt, typename RhoAt>
+__device__ __forceinline__ void emit_byte(const int32_t* __restrict__ vi, WAt w_at, RhoAt rho_at,
+                                          uint16_t* __restrict__ vals_out, uint8_t* __restrict__ nm_out) {
+  uint16_t out[4];
+  uint32_t byte = 0;
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    uint16_t w[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) w[q] = w_at(vi[4 * g + q]);
+    uint32_t p0, p1;
+    if constexpr (SCORED) {
+      float sc[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) sc[q] = rho_at(vi[4 * g + q]);
+      top2_of_4_scores(sc, p0, p1);
+    } else {
+      top2_of_4(w, p0, p1);
+    }
+    out[2 * g] = w[p0];
+    out[2 * g + 1] = w[p1];
+    byte |= (p0 | (p1 << 2)) << (4 * g);
+  }
+  uint2 packed;
+  packed.x = (uint32_t)out[0] | ((uint32_t)out[1] << 16);
+  packed.y = (uint32_t)out[2] | ((uint32_t)out[3] << 16);
+  *reinterpret_cast<uint2*>(vals_out) = packed;
+  *nm_out = (uint8_t)byte;
+}
+
+template <bool SCORED>
 __global__ __launch_bounds__(kEmitThreads) void emit_kernel(const uint16_t* __restrict__ W,
+                                                            const float* __restrict__ rho,
                                                             const int32_t* __restrict__ vec_idx,
                                                             uint16_t* __restrict__ vals, uint8_t* __restrict__ nm_idx,
                                                             int M, int K, int V, int Kv) {
@@ -224,26 +317,29 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(const uint16_t* __re
   const int r = (int)(id / bytes_per_row);
   const int b = (int)(id % bytes_per_row);
   const int t = r / V;
-  const int32_t* vi = vec_idx + (size_t)t * Kv + 8 * b;
   const uint16_t* wr = W + (size_t)r * K;
-  uint16_t out[4];
-  uint32_t byte = 0;
+  const float* rr = SCORED ? rho + (size_t)r * K : nullptr;
+  emit_byte<SCORED>(
+      vec_idx + (size_t)t * Kv + 8 * b, [&](int c) { return wr[c]; }, [&](int c) { return rr[c]; },
+      vals + (size_t)r * (Kv / 2) + 4 * b, nm_idx + (size_t)r * bytes_per_row + b);
+}
+
+// Vector pruning alone: vals_v[r][j] = W[r][vec_idx[t][j]], eight outputs per thread.
+__global__ __launch_bounds__(kEmitThreads) void gather_kernel(const uint16_t* __restrict__ W,
+                                                              const int32_t* __restrict__ vec_idx,
+                                                              uint16_t* __restrict__ vals_v, int M, int K, int V,
+                                                              int Kv) {
+  const int pieces_per_row = Kv / 8;
+  const int64_t id = (int64_t)blockIdx.x * kEmitThreads + threadIdx.x;
+  if (id >= (int64_t)M * pieces_per_row) return;
+  const int r = (int)(id / pieces_per_row);
+  const int b = (int)(id % pieces_per_row);
+  const int32_t* vi = vec_idx + (size_t)(r / V) * Kv + 8 * b;
+  const uint16_t* wr = W + (size_t)r * K;
+  uint32_t o[4];
 #pragma unroll
-  for (int g = 0; g < 2; ++g) {
-    uint16_t w[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) w[q] = wr[vi[4 * g + q]];
-    uint32_t p0, p1;
-    top2_of_4(w, p0, p1);
-    out[2 * g] = w[p0];
-    out[2 * g + 1] = w[p1];
-    byte |= (p0 | (p1 << 2)) << (4 * g);
-  }
-  uint2 packed;
-  packed.x = (uint32_t)out[0] | ((uint32_t)out[1] << 16);
-  packed.y = (uint32_t)out[2] | ((uint32_t)out[3] << 16);
-  *reinterpret_cast<uint2*>(vals + (size_t)r * (Kv / 2) + 4 * b) = packed;
-  nm_idx[(size_t)r * bytes_per_row + b] = (uint8_t)byte;
+  for (int q = 0; q < 4; ++q) o[q] = (uint32_t)wr[vi[2 * q]] | ((uint32_t)wr[vi[2 * q + 1]] << 16);
+  *reinterpret_cast<uint4*>(vals_v + (size_t)r * Kv + 8 * b) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -271,49 +367,69 @@ __global__ __launch_bounds__(256) void scatter_kernel(const uint16_t* __restrict
   wr[vi[(nib >> 2) & 3u]] = vals[(size_t)r * (Kv / 2) + 2 * g + 1];
 }
 
-// The same emission with the row of W staged in LDS: one workgroup per row reads the row once, fully
-// coalesced, and picks the kept columns from LDS.  The picks of emit_kernel go to global memory,
-// which costs one address-unit cycle per lane and is slow as soon as the vector index is not
-// ascending (a caller-given tile order).  Needs 2 K bytes of LDS.
+// The same emission with the row of W (and of rho) staged in LDS: one workgroup per row reads the
+// row once, fully coalesced, and picks the kept columns from LDS.  The picks of emit_kernel go to
+// global memory, which costs one address-unit cycle per lane and is slow as soon as the vector
+// index is not ascending (a caller-given tile order).  Needs 2 K bytes of LDS, 6 K with scores.
 constexpr int kEmitRowMaxK = 32 * 1024;
+constexpr int kEmitRowScoredMaxK = 16 * 1024;
 
-__global__ __launch_bounds__(kEmitThreads) void emit_rows_kernel(const uint16_t* __restrict__ W,
-                                                                 const int32_t* __restrict__ vec_idx,
-                                                                 uint16_t* __restrict__ vals,
-                                                                 uint8_t* __restrict__ nm_idx, int K, int V, int Kv,
-                                                                 bool vec8) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t row[];  // K elements
-  const int r = blockIdx.x;
-  const int t = r / V;
-  const uint16_t* wr = W + (size_t)r * K;
-  if (vec8) {  // K % 8 == 0 and W 16-byte aligned
+__device__ __forceinline__ void stage_row(uint16_t* row, const uint16_t* __restrict__ wr, int K, bool vec8) {
+  if (vec8) {  // K % 8 == 0 and the source 16-byte aligned
     for (int i = threadIdx.x; i < K / 8; i += kEmitThreads)
       reinterpret_cast<uint4*>(row)[i] = reinterpret_cast<const uint4*>(wr)[i];
   } else {
     for (int i = threadIdx.x; i < K; i += kEmitThreads) row[i] = wr[i];
   }
+}
+
+template <bool SCORED>
+__global__ __launch_bounds__(kEmitThreads) void emit_rows_kernel(const uint16_t* __restrict__ W,
+                                                                 const float* __restrict__ rho,
+                                                                 const int32_t* __restrict__ vec_idx,
+                                                                 uint16_t* __restrict__ vals,
+                                                                 uint8_t* __restrict__ nm_idx, int K, int V, int Kv,
+                                                                 bool vec8, bool rho_vec4) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t emit_lds[];
+  const int K8 = (K + 7) / 8 * 8;
+  float* score_row = reinterpret_cast<float*>(emit_lds);                     // K floats, only when SCORED
+  uint16_t* row = reinterpret_cast<uint16_t*>(emit_lds + (SCORED ? (size_t)K8 * 4 : 0));  // K elements
+  const int r = blockIdx.x;
+  const int t = r / V;
+  stage_row(row, W + (size_t)r * K, K, vec8);
+  if constexpr (SCORED) {
+    const float* rr = rho + (size_t)r * K;
+    if (rho_vec4) {  // K % 4 == 0 and rho 16-byte aligned
+      for (int i = threadIdx.x; i < K / 4; i += kEmitThreads)
+        reinterpret_cast<float4*>(score_row)[i] = reinterpret_cast<const float4*>(rr)[i];
+    } else {
+      for (int i = threadIdx.x; i < K; i += kEmitThreads) score_row[i] = rr[i];
+    }
+  }
   __syncthreads();
   const int bytes_per_row = Kv / 8;
-  for (int b = threadIdx.x; b < bytes_per_row; b += kEmitThreads) {
-    const int32_t* vi = vec_idx + (size_t)t * Kv + 8 * b;
-    uint16_t out[4];
-    uint32_t byte = 0;
+  for (int b = threadIdx.x; b < bytes_per_row; b += kEmitThreads)
+    emit_byte<SCORED>(
+        vec_idx + (size_t)t * Kv + 8 * b, [&](int c) { return row[c]; }, [&](int c) { return score_row[c]; },
+        vals + (size_t)r * (Kv / 2) + 4 * b, nm_idx + (size_t)r * bytes_per_row + b);
+}
+
+__global__ __launch_bounds__(kEmitThreads) void gather_rows_kernel(const uint16_t* __restrict__ W,
+                                                                   const int32_t* __restrict__ vec_idx,
+                                                                   uint16_t* __restrict__ vals_v, int K, int V, int Kv,
+                                                                   bool vec8) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t emit_lds[];
+  uint16_t* row = reinterpret_cast<uint16_t*>(emit_lds);
+  const int r = blockIdx.x;
+  stage_row(row, W + (size_t)r * K, K, vec8);
+  __syncthreads();
+  const int32_t* vt = vec_idx + (size_t)(r / V) * Kv;
+  for (int b = threadIdx.x; b < Kv / 8; b += kEmitThreads) {
+    const int32_t* vi = vt + 8 * b;
+    uint32_t o[4];
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
-      uint16_t w[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) w[q] = row[vi[4 * g + q]];
-      uint32_t p0, p1;
-      top2_of_4(w, p0, p1);
-      out[2 * g] = w[p0];
-      out[2 * g + 1] = w[p1];
-      byte |= (p0 | (p1 << 2)) << (4 * g);
-    }
-    uint2 packed;
-    packed.x = (uint32_t)out[0] | ((uint32_t)out[1] << 16);
-    packed.y = (uint32_t)out[2] | ((uint32_t)out[3] << 16);
-    *reinterpret_cast<uint2*>(vals + (size_t)r * (Kv / 2) + 4 * b) = packed;
-    nm_idx[(size_t)r * bytes_per_row + b] = (uint8_t)byte;
+    for (int q = 0; q < 4; ++q) o[q] = (uint32_t)row[vi[2 * q]] | ((uint32_t)row[vi[2 * q + 1]] << 16);
+    *reinterpret_cast<uint4*>(vals_v + (size_t)r * Kv + 8 * b) = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 
@@ -367,42 +483,78 @@ __global__ __launch_bounds__(kOrderThreads) void order_kernel(const int32_t* __r
 
 }  // namespace
 
-hipError_t launch_pack(const hinm_shape& s, const void* W, const int32_t* tile_order, void* vals, uint8_t* nm_idx,
-                       int32_t* vec_idx, double* scores, hipStream_t stream) {
+template <typename Kernel>
+hipError_t allow_lds(Kernel kernel, size_t bytes) {
+  if (bytes <= 64 * 1024) return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes);
+}
+
+hipError_t launch_pack(const PackArgs& a, hipStream_t stream) {
+  const hinm_shape& s = a.s;
   const int T = s.M / s.V;
-  const uint16_t* Wb = static_cast<const uint16_t*>(W);
-  const bool vec8 = (s.K % 8 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15u) == 0);
-  const int cols_per_thread = vec8 ? 8 : 1;
+  const uint16_t* Wb = static_cast<const uint16_t*>(a.W);
+  uint16_t* vals = static_cast<uint16_t*>(a.vals);
+  const bool vec8 = (s.K % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.W) & 15u) == 0);
+  const bool rho_vec4 = a.rho && (s.K % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.rho) & 15u) == 0);
+  // ---- score
+  const int cols_per_thread = a.rho ? (rho_vec4 ? 4 : 1) : (vec8 ? 8 : 1);
   const int threads_needed = (s.K + cols_per_thread - 1) / cols_per_thread;
   dim3 grid((threads_needed + kScoreThreads - 1) / kScoreThreads, T);
-  if (s.dtype == HINM_F16) {
-    if (vec8) score_kernel<HINM_F16, 8><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
-    else score_kernel<HINM_F16, 1><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
+  if (a.rho) {
+    if (rho_vec4) score_rho_kernel<4><<<grid, kScoreThreads, 0, stream>>>(a.rho, a.scores, s.K, s.V);
+    else score_rho_kernel<1><<<grid, kScoreThreads, 0, stream>>>(a.rho, a.scores, s.K, s.V);
+  } else if (s.dtype == HINM_F16) {
+    if (vec8) score_kernel<HINM_F16, 8><<<grid, kScoreThreads, 0, stream>>>(Wb, a.scores, s.K, s.V);
+    else score_kernel<HINM_F16, 1><<<grid, kScoreThreads, 0, stream>>>(Wb, a.scores, s.K, s.V);
   } else {
-    if (vec8) score_kernel<HINM_BF16, 8><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
-    else score_kernel<HINM_BF16, 1><<<grid, kScoreThreads, 0, stream>>>(Wb, scores, s.K, s.V);
+    if (vec8) score_kernel<HINM_BF16, 8><<<grid, kScoreThreads, 0, stream>>>(Wb, a.scores, s.K, s.V);
+    else score_kernel<HINM_BF16, 1><<<grid, kScoreThreads, 0, stream>>>(Wb, a.scores, s.K, s.V);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (s.K <= 4 * kSelectThreads) select_kernel<4><<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
-  else if (s.K <= 16 * kSelectThreads) select_kernel<16><<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
-  else select_kernel<0><<<T, kSelectThreads, 0, stream>>>(scores, vec_idx, s.K, s.Kv);
+  // ---- select
+  if (s.K <= 4 * kSelectThreads) select_kernel<4><<<T, kSelectThreads, 0, stream>>>(a.scores, a.vec_idx, s.K, s.Kv);
+  else if (s.K <= 16 * kSelectThreads) select_kernel<16><<<T, kSelectThreads, 0, stream>>>(a.scores, a.vec_idx, s.K, s.Kv);
+  else select_kernel<0><<<T, kSelectThreads, 0, stream>>>(a.scores, a.vec_idx, s.K, s.Kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (tile_order) {
-    order_kernel<<<T, kOrderThreads, (size_t)((s.K + 31) / 32) * 4, stream>>>(tile_order, vec_idx, s.K, s.Kv);
+  // ---- order
+  if (a.tile_order) {
+    order_kernel<<<T, kOrderThreads, (size_t)((s.K + 31) / 32) * 4, stream>>>(a.tile_order, a.vec_idx, s.K, s.Kv);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  // rows long enough to fill a workgroup go through LDS; short rows keep the flat kernel
-  if (s.K <= kEmitRowMaxK && s.Kv >= 8 * kEmitThreads) {
-    emit_rows_kernel<<<(unsigned)s.M, kEmitThreads, (size_t)((s.K + 7) / 8 * 8) * 2, stream>>>(
-        Wb, vec_idx, static_cast<uint16_t*>(vals), nm_idx, s.K, s.V, s.Kv, vec8);
-    return hipGetLastError();
+  // ---- emit (or gather): rows long enough to fill a workgroup go through LDS, short rows keep the
+  // flat kernels
+  const size_t row_bytes = (size_t)((s.K + 7) / 8 * 8) * 2;
+  const bool long_rows = s.Kv >= 8 * kEmitThreads;
+  const int64_t flat_threads = (int64_t)s.M * (s.Kv / 8);
+  const unsigned flat_blocks = (unsigned)((flat_threads + kEmitThreads - 1) / kEmitThreads);
+  if (!a.nm_idx) {
+    if (long_rows && s.K <= kEmitRowMaxK)
+      gather_rows_kernel<<<(unsigned)s.M, kEmitThreads, row_bytes, stream>>>(Wb, a.vec_idx, vals, s.K, s.V, s.Kv, vec8);
+    else
+      gather_kernel<<<flat_blocks, kEmitThreads, 0, stream>>>(Wb, a.vec_idx, vals, s.M, s.K, s.V, s.Kv);
+  } else if (a.rho) {
+    if (long_rows && s.K <= kEmitRowScoredMaxK) {
+      const size_t lds_bytes = 3 * row_bytes;
+      e = allow_lds(emit_rows_kernel<true>, lds_bytes);
+      if (e != hipSuccess) return e;
+      emit_rows_kernel<true><<<(unsigned)s.M, kEmitThreads, lds_bytes, stream>>>(Wb, a.rho, a.vec_idx, vals, a.nm_idx,
+                                                                                 s.K, s.V, s.Kv, vec8, rho_vec4);
+    } else {
+      emit_kernel<true><<<flat_blocks, kEmitThreads, 0, stream>>>(Wb, a.rho, a.vec_idx, vals, a.nm_idx, s.M, s.K, s.V,
+                                                                  s.Kv);
+    }
+  } else {
+    if (long_rows && s.K <= kEmitRowMaxK)
+      emit_rows_kernel<false><<<(unsigned)s.M, kEmitThreads, row_bytes, stream>>>(Wb, nullptr, a.vec_idx, vals,
+                                                                                  a.nm_idx, s.K, s.V, s.Kv, vec8, false);
+    else
+      emit_kernel<false><<<flat_blocks, kEmitThreads, 0, stream>>>(Wb, nullptr, a.vec_idx, vals, a.nm_idx, s.M, s.K,
+                                                                   s.V, s.Kv);
   }
-  const int64_t emit_threads = (int64_t)s.M * (s.Kv / 8);
-  emit_kernel<<<(unsigned)((emit_threads + kEmitThreads - 1) / kEmitThreads), kEmitThreads, 0, stream>>>(
-      Wb, vec_idx, static_cast<uint16_t*>(vals), nm_idx, s.M, s.K, s.V, s.Kv);
   return hipGetLastError();
 }
 

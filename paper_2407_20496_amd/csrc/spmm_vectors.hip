@@ -1,0 +1,345 @@
+// Product of a layer that carries the column-vector mask alone (arXiv 2407.20496, Section 3.1 first
+// step; Section 5.1.2: during gradual pruning a layer stays in this state until the target vector
+// sparsity is reached and only then receives the 2:4 mask), with the same fused channel orders as
+// the HiNM product (Section 3.2, Section 5.3):
+//     Y[pi_out[r]][n] = sum_j vals_v[r][j] * X[pi_in[vec_idx[r / V][j]]][n].
+// Every surviving entry is stored, so this is a dense contraction over the gathered input rows and
+// runs on the dense 32x32x16 MFMA.
+//
+// One workgroup computes one tile of V = 32 * RB consecutive output channels for a block of 256
+// columns, in steps of 32 kept columns:
+//   global -> LDS : the 32 input rows named by the vector index composed with pi_in (each a
+//                   contiguous 512-byte row segment) and the tile's 32 stored values per row;
+//   LDS -> MFMA   : every wave owns 64 of the 256 columns and all V rows; A fragments are plain
+//                   16-byte LDS reads, B fragments use the transposing LDS read;
+//   epilogue      : fp32 accumulators -> optional ReLU -> 16-bit, staged through LDS so that every
+//                   output row leaves as one contiguous 512-byte segment to row pi_out[r] of Y.
+// Global loads for step s+1 are in flight while step s is multiplied (registers -> other LDS stage).
+// A plain kernel (one thread per output) covers every other legal shape and serves as cross-check.
+#include "hinm_internal.h"
+#include "mfma_types.h"
+
+namespace hinm {
+namespace {
+
+// Operand layout of the dense 32x32x16 MFMA (lane l): A holds row l % 32, k = 8 * (l / 32) + 0..7;
+// B holds column l % 32, the same eight k; D as for the sparse 32x32 form.
+template <int DT>
+__device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
+  if constexpr (DT == HINM_F16) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
+                                                  0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+  }
+}
+
+constexpr int kNB = 256;  // columns per workgroup
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr int kCB = 2;                  // 32-column blocks per wave
+constexpr int kKS = 32;                 // kept columns per step
+constexpr int kBStride = kNB * 2 + 64;  // bytes per gathered row in LDS (+64: rows 4 apart hit distinct banks)
+constexpr int kYStride = kNB * 2 + 16;  // bytes per staged output row
+constexpr int kAStride = kKS * 2 + 16;  // 80: 16 consecutive rows hit 16 distinct 16-byte bank groups
+constexpr int kBBytes = kKS * kBStride;
+
+__host__ __device__ constexpr int stage_bytes(int V) { return kBBytes + V * kAStride; }
+__host__ __device__ constexpr int total_lds_bytes(int V) {
+  const int two = 2 * stage_bytes(V);
+  const int epi = V * kYStride;
+  return two > epi ? two : epi;
+}
+
+template <int DT, int RB>
+__global__ __launch_bounds__(kThreads) void spmm_vectors_kernel(
+    const uint16_t* __restrict__ vals_v, const int32_t* __restrict__ vec_idx, const int32_t* __restrict__ pi_in,
+    const int32_t* __restrict__ pi_out, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y,
+    int64_t ldy, int T, int Kv, int N, int n_blocks, int work_per_xcd, bool relu, bool out_f32) {
+  constexpr int V = 32 * RB;
+  constexpr int B_PIECES = kKS / 8;             // 16-byte pieces of B per thread and step
+  constexpr int A_PIECES_TOTAL = V * kKS / 8;   // 16-byte pieces of stored values per step
+  constexpr int A_PIECES = (A_PIECES_TOTAL + kThreads - 1) / kThreads;
+
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+  // consecutive workgroup ids go to different XCDs: give every XCD a contiguous run of the
+  // column-block-major work list, so the tiles running together share one column panel of X in L2
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int work = xcd * work_per_xcd + slot;
+  if (slot >= work_per_xcd || work >= n_blocks * T) return;
+  const int nb = work / T;
+  const int t = work % T;
+  const int n0 = nb * kNB;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int steps = (Kv + kKS - 1) / kKS;
+
+  const int32_t* vi = vec_idx + (size_t)t * Kv;
+  const uint16_t* vtile = vals_v + (size_t)t * V * Kv;
+
+  // B piece q of this thread: row 8 q + tid / 32 of the step, 16-byte column chunk tid % 32
+  const int b_row0 = tid >> 5;
+  const int b_chunk = tid & 31;
+  const bool b_cols_ok = n0 + b_chunk * 8 < N;  // chunk starts inside the matrix (ldx % 8 == 0 keeps it in bounds)
+
+  u32x4 b_regs[B_PIECES];
+  u32x4 a_regs[A_PIECES];
+  int g_next[B_PIECES];   // X rows of step s + 1
+  int g_next2[B_PIECES];  // X rows of step s + 2 (after pi_in)
+  int v_next3[B_PIECES];  // vector-index entries of step s + 3
+
+  auto load_vec_idx = [&](int step, int (&out)[B_PIECES]) {
+#pragma unroll
+    for (int q = 0; q < B_PIECES; ++q) {
+      const int j = step * kKS + 8 * q + b_row0;
+      out[q] = (j < Kv) ? vi[j] : -1;
+    }
+  };
+  auto apply_pi_in = [&](const int (&in)[B_PIECES], int (&out)[B_PIECES]) {
+#pragma unroll
+    for (int q = 0; q < B_PIECES; ++q) out[q] = (in[q] >= 0 && pi_in) ? pi_in[in[q]] : in[q];
+  };
+  auto load_step = [&](int step, const int (&rows)[B_PIECES]) {
+#pragma unroll
+    for (int q = 0; q < B_PIECES; ++q) {
+      b_regs[q] = u32x4{0, 0, 0, 0};
+      if (rows[q] >= 0 && b_cols_ok)
+        b_regs[q] = *reinterpret_cast<const u32x4*>(X + (size_t)rows[q] * ldx + n0 + b_chunk * 8);
+    }
+#pragma unroll
+    for (int q = 0; q < A_PIECES; ++q) {
+      const int p = tid + q * kThreads;
+      a_regs[q] = u32x4{0, 0, 0, 0};
+      if (p < A_PIECES_TOTAL) {
+        const int row = p / (kKS / 8), c = p % (kKS / 8);  // 16-byte piece c of the row's 64 bytes
+        const int j0 = step * kKS + c * 8;                  // first kept column of the piece
+        if (j0 + 8 <= Kv)                                    // whole piece inside the row (Kv % 8 == 0)
+          a_regs[q] = *reinterpret_cast<const u32x4*>(vtile + (size_t)row * Kv + j0);
+      }
+    }
+  };
+  auto store_step = [&](uint8_t* stage) {
+    uint8_t* bs = stage;
+    uint8_t* as = stage + kBBytes;
+#pragma unroll
+    for (int q = 0; q < B_PIECES; ++q)
+      *reinterpret_cast<u32x4*>(bs + (8 * q + b_row0) * kBStride + b_chunk * 16) = b_regs[q];
+#pragma unroll
+    for (int q = 0; q < A_PIECES; ++q) {
+      const int p = tid + q * kThreads;
+      if (p < A_PIECES_TOTAL) {
+        const int row = p / (kKS / 8), c = p % (kKS / 8);
+        *reinterpret_cast<u32x4*>(as + row * kAStride + c * 16) = a_regs[q];
+      }
+    }
+  };
+
+  const int i32 = lane & 31;  // A row / B column inside a 32-block
+  const int qh = lane >> 5;   // which eight k of the substep this lane holds
+  const int i16 = lane & 15;
+  f32x16 acc[RB][kCB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[rb][cb][e] = 0.f;
+
+  auto compute_step = [&](const uint8_t* stage) {
+    const uint8_t* bs = stage;
+    const uint8_t* as = stage + kBBytes;
+#pragma unroll
+    for (int sub = 0; sub < kKS / 16; ++sub) {
+      u32x4 a[RB];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        a[rb] = *reinterpret_cast<const u32x4*>(as + (32 * rb + i32) * kAStride + sub * 32 + qh * 16);
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) {
+        // B slots 4 u .. 4 u + 3 <- rows 16 sub + 8 qh + 4 u + (0..3) of the step, column of this lane
+        u32x4 b;
+        const int col_byte = (wave * 64 + cb * 32 + (i32 & 16) + (i16 & 3) * 4) * 2;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int row = sub * 16 + 8 * qh + 4 * u + (i16 >> 2);
+          const u32x2 v = lds_read_tr16(bs + row * kBStride + col_byte);
+          b[2 * u] = v.x;
+          b[2 * u + 1] = v.y;
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) acc[rb][cb] = mfma_32x32x16<DT>(a[rb], b, acc[rb][cb]);
+      }
+    }
+  };
+
+  uint8_t* stage0 = lds;
+  uint8_t* stage1 = lds + stage_bytes(V);
+  {
+    int v0[B_PIECES], v1[B_PIECES], v2[B_PIECES];
+    load_vec_idx(0, v0);
+    load_vec_idx(1, v1);
+    load_vec_idx(2, v2);
+    int g0[B_PIECES];
+    apply_pi_in(v0, g0);
+    apply_pi_in(v1, g_next);
+    apply_pi_in(v2, g_next2);
+    load_vec_idx(3, v_next3);
+    load_step(0, g0);
+    store_step(stage0);
+  }
+  __syncthreads();
+  for (int s = 0; s < steps; ++s) {
+    uint8_t* cur = (s & 1) ? stage1 : stage0;
+    uint8_t* nxt = (s & 1) ? stage0 : stage1;
+    const bool more = s + 1 < steps;
+    if (more) load_step(s + 1, g_next);
+    // rotate the index pipeline: rows of step s+2 are ready, translate step s+3, fetch step s+4
+#pragma unroll
+    for (int q = 0; q < B_PIECES; ++q) g_next[q] = g_next2[q];
+    apply_pi_in(v_next3, g_next2);
+    load_vec_idx(s + 4, v_next3);
+    compute_step(cur);
+    if (more) store_step(nxt);
+    __syncthreads();
+  }
+
+  // D layout: lane holds column lane % 32, rows 8 * (reg / 4) + 4 * (lane / 32) + reg % 4.
+  if (out_f32) {
+    float* Yf = static_cast<float*>(Y);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = t * V + 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
+        const int64_t out_row = pi_out ? pi_out[r] : r;
+#pragma unroll
+        for (int cb = 0; cb < kCB; ++cb) {
+          const int n = n0 + wave * 64 + cb * 32 + i32;
+          float v = acc[rb][cb][e];
+          if (relu) v = v > 0.f ? v : 0.f;
+          if (n < N) Yf[out_row * ldy + n] = v;
+        }
+      }
+    return;
+  }
+  // the last loop iteration ended with a barrier: both stages are free
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
+        const int col = wave * 64 + cb * 32 + i32;
+        float v = acc[rb][cb][e];
+        if (relu) v = v > 0.f ? v : 0.f;
+        *reinterpret_cast<uint16_t*>(lds + row * kYStride + col * 2) = float_to_bits<DT>(v);
+      }
+  __syncthreads();
+  uint16_t* Yh = static_cast<uint16_t*>(Y);
+  // 32 lanes move one 512-byte row; a wave moves two rows per pass
+  for (int row = (tid >> 5); row < V; row += kThreads / 32) {
+    const int r = t * V + row;
+    const int64_t out_row = pi_out ? pi_out[r] : r;
+    const int n = n0 + b_chunk * 8;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * kYStride + b_chunk * 16);
+    uint16_t* dst = Yh + out_row * ldy + n;
+    if (n + 8 <= N) {
+      *reinterpret_cast<u32x4*>(dst) = v;
+    } else if (n < N) {
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      for (int e = 0; e < N - n; ++e) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+    }
+  }
+}
+
+// One thread per output element, fp32 fused multiply-adds in ascending vector-index order.
+template <int DT>
+__global__ __launch_bounds__(256) void spmm_vectors_plain_kernel(
+    const uint16_t* __restrict__ vals_v, const int32_t* __restrict__ vec_idx, const int32_t* __restrict__ pi_in,
+    const int32_t* __restrict__ pi_out, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y,
+    int64_t ldy, int M, int V, int Kv, int N, bool relu, bool out_f32) {
+  const int n = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int r = blockIdx.y * 4 + (threadIdx.x >> 6);
+  if (n >= N || r >= M) return;
+  const uint16_t* vr = vals_v + (size_t)r * Kv;
+  const int32_t* vi = vec_idx + (size_t)(r / V) * Kv;
+  float acc = 0.f;
+  for (int j = 0; j < Kv; ++j) {
+    int c = vi[j];
+    if (pi_in) c = pi_in[c];
+    acc = __builtin_fmaf(bits_to_float<DT>(vr[j]), bits_to_float<DT>(X[(size_t)c * ldx + n]), acc);
+  }
+  if (relu) acc = acc > 0.f ? acc : 0.f;
+  const int64_t row = pi_out ? pi_out[r] : r;
+  if (out_f32) static_cast<float*>(Y)[row * ldy + n] = acc;
+  else static_cast<uint16_t*>(Y)[row * ldy + n] = float_to_bits<DT>(acc);
+}
+
+template <int DT, int RB>
+hipError_t launch_one(const VectorsArgs& a, hipStream_t stream) {
+  constexpr int V = 32 * RB;
+  const int T = a.s.M / V;
+  const int n_blocks = (a.N + kNB - 1) / kNB;
+  const int64_t work = (int64_t)n_blocks * T;
+  const int work_per_xcd = (int)((work + 7) / 8);
+  const size_t lds_bytes = total_lds_bytes(V);
+  auto kernel = spmm_vectors_kernel<DT, RB>;
+  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  kernel<<<dim3((unsigned)(work_per_xcd * 8)), kThreads, lds_bytes, stream>>>(
+      static_cast<const uint16_t*>(a.vals_v), a.vec_idx, a.pi_in, a.pi_out, static_cast<const uint16_t*>(a.X), a.ldx,
+      a.Y, a.ldy, T, a.s.Kv, a.N, n_blocks, work_per_xcd, a.relu, a.out_f32);
+  return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_dt(const VectorsArgs& a, hipStream_t stream) {
+  switch (a.s.V) {
+    case 32: return launch_one<DT, 1>(a, stream);
+    case 64: return launch_one<DT, 2>(a, stream);
+    case 96: return launch_one<DT, 3>(a, stream);
+    case 128: return launch_one<DT, 4>(a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+bool spmm_vectors_mfma_supported(const VectorsArgs& a) {
+  const int V = a.s.V;
+  if (!(V == 32 || V == 64 || V == 96 || V == 128)) return false;
+  if (a.ldx % 8 != 0 || a.ldy % 8 != 0) return false;
+  const int64_t work = (int64_t)((a.N + kNB - 1) / kNB) * (a.s.M / V);
+  return work < (1ll << 28);
+}
+
+hipError_t launch_spmm_vectors_mfma(const VectorsArgs& a, hipStream_t stream) {
+  return a.s.dtype == HINM_F16 ? launch_dt<HINM_F16>(a, stream) : launch_dt<HINM_BF16>(a, stream);
+}
+
+hipError_t launch_spmm_vectors_plain(const VectorsArgs& a, hipStream_t stream) {
+  dim3 grid((a.N + 63) / 64, (a.s.M + 3) / 4);
+  if (grid.y > 65535u) return hipErrorInvalidConfiguration;
+  auto v = static_cast<const uint16_t*>(a.vals_v);
+  auto x = static_cast<const uint16_t*>(a.X);
+  if (a.s.dtype == HINM_F16)
+    spmm_vectors_plain_kernel<HINM_F16><<<grid, 256, 0, stream>>>(v, a.vec_idx, a.pi_in, a.pi_out, x, a.ldx, a.Y, a.ldy,
+                                                                  a.s.M, a.s.V, a.s.Kv, a.N, a.relu, a.out_f32);
+  else
+    spmm_vectors_plain_kernel<HINM_BF16><<<grid, 256, 0, stream>>>(v, a.vec_idx, a.pi_in, a.pi_out, x, a.ldx, a.Y,
+                                                                   a.ldy, a.s.M, a.s.V, a.s.Kv, a.N, a.relu, a.out_f32);
+  return hipGetLastError();
+}
+
+}  // namespace hinm

@@ -35,8 +35,13 @@ class Packed:
                 self.vec_idx.cpu().numpy().reshape(self.M // self.V, self.Kv))
 
 
-def gpu_pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, W_dev=None, sigma=None) -> Packed:
-    """hinm_pack, or hinm_pack_ordered when sigma (int [T, K], per-tile channel order) is given."""
+def dev_f32(a) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+
+
+def gpu_pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, W_dev=None, sigma=None, rho=None) -> Packed:
+    """hinm_pack; hinm_pack_ordered when sigma (int [T, K], per-tile channel order) is given;
+    hinm_pack_scored when rho (float32 [M, K], per-weight saliency) is given (sigma optional)."""
     M, K = W_bits.shape
     vb, nb, cb, wb = hinm.hinm_pack_sizes(M, K, V, Kv, dtype)
     Wd = dev_bits(W_bits) if W_dev is None else W_dev
@@ -44,12 +49,63 @@ def gpu_pack(W_bits: np.ndarray, dtype: str, V: int, Kv: int, W_dev=None, sigma=
     nm = torch.empty(nb, dtype=torch.uint8, device=DEV)
     vec = torch.empty(cb // 4, dtype=torch.int32, device=DEV)
     ws = torch.empty(wb // 8, dtype=torch.float64, device=DEV)
-    if sigma is None:
+    sig = None if sigma is None else dev_i32(sigma)
+    if rho is not None:
+        hinm.hinm_pack_scored(M, K, V, Kv, dtype, Wd, dev_f32(rho), sig, vals, nm, vec, ws, wb)
+    elif sigma is None:
         hinm.hinm_pack(M, K, V, Kv, dtype, Wd, vals, nm, vec, ws, wb)
     else:
-        hinm.hinm_pack_ordered(M, K, V, Kv, dtype, Wd, dev_i32(sigma), vals, nm, vec, ws, wb)
+        hinm.hinm_pack_ordered(M, K, V, Kv, dtype, Wd, sig, vals, nm, vec, ws, wb)
     torch.cuda.synchronize()
     return Packed(M, K, V, Kv, dtype, vals, nm, vec)
+
+
+class VectorPacked:
+    """A layer with the column-vector mask alone: vals_v [M][Kv], vec_idx [T][Kv]."""
+
+    def __init__(self, M, K, V, Kv, dtype, vals_v, vec_idx):
+        self.M, self.K, self.V, self.Kv, self.dtype = M, K, V, Kv, dtype
+        self.vals_v, self.vec_idx = vals_v, vec_idx
+
+    def host(self):
+        return (host_bits(self.vals_v).reshape(self.M, self.Kv),
+                self.vec_idx.cpu().numpy().reshape(self.M // self.V, self.Kv))
+
+
+def gpu_pack_vectors(W_bits: np.ndarray, dtype: str, V: int, Kv: int, sigma=None, rho=None) -> VectorPacked:
+    M, K = W_bits.shape
+    _, _, cb, wb = hinm.hinm_pack_sizes(M, K, V, Kv, dtype)
+    vals_v = torch.full((M * Kv,), 0x7B7B, dtype=torch.int16, device=DEV)
+    vec = torch.empty(cb // 4, dtype=torch.int32, device=DEV)
+    ws = torch.empty(wb // 8, dtype=torch.float64, device=DEV)
+    hinm.hinm_pack_vectors(M, K, V, Kv, dtype, dev_bits(W_bits), None if rho is None else dev_f32(rho),
+                           None if sigma is None else dev_i32(sigma), vals_v, vec, ws, wb)
+    torch.cuda.synchronize()
+    return VectorPacked(M, K, V, Kv, dtype, vals_v, vec)
+
+
+def gpu_spmm_vectors(p: VectorPacked, X_bits: np.ndarray, pi_in, pi_out, flags=0, ldx=None, ldy=None):
+    """Returns uint16 bits [M, N], or float32 [M, N] with OUT_F32."""
+    K, N = X_bits.shape
+    ldx = ldx or (N if N == 1 else (N + 7) // 8 * 8)
+    ldy = ldy or (N if N == 1 else (N + 7) // 8 * 8)
+    Xp = np.zeros((K, ldx), dtype=np.uint16)
+    Xp[:, :N] = X_bits
+    X_dev = dev_bits(Xp)
+    f32 = bool(flags & hinm.OUT_F32)
+    Y = (torch.full((p.M, ldy), float("nan"), dtype=torch.float32, device=DEV) if f32
+         else torch.full((p.M, ldy), 0x7B7B, dtype=torch.int16, device=DEV))
+    hinm.hinm_spmm_vectors(p.M, p.K, p.V, p.Kv, p.dtype, N, p.vals_v, p.vec_idx,
+                           None if pi_in is None else dev_i32(pi_in), None if pi_out is None else dev_i32(pi_out),
+                           X_dev, ldx, Y, ldy, flags)
+    torch.cuda.synchronize()
+    if f32:
+        out = Y.cpu().numpy()
+        assert np.all(np.isnan(out[:, N:])), "columns beyond N were written"
+        return out[:, :N].copy()
+    out = host_bits(Y)
+    assert np.all(out[:, N:] == 0x7B7B), "columns beyond N were written"
+    return out[:, :N].copy()
 
 
 def upload_packed(M, K, V, Kv, dtype, vals, nm_idx, vec_idx) -> Packed:

@@ -67,6 +67,23 @@ def test_null_and_workspace_errors_are_reported_before_any_launch():
     assert lib.hinm_pack_ordered(C.byref(sh), fake, fake + 2, fake, fake, fake, fake, 1 << 20, None) == 5
     big = binding._Shape(16, 400000, 16, 8, 0)
     assert lib.hinm_pack_ordered(C.byref(big), fake, fake, fake, fake, fake, fake, 1 << 30, None) == 5
+    # scored pack: null rho, misaligned rho; vector-only pack: misaligned vals_v, rho optional (checks go on to
+    # the workspace); vector-only product: null, bad N, bad ld, misaligned vals_v, a flag it does not know
+    assert lib.hinm_pack_scored(C.byref(sh), fake, None, None, fake, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.hinm_pack_scored(C.byref(sh), fake, fake + 2, None, fake, fake, fake, fake, 1 << 20, None) == 2
+    assert lib.hinm_pack_scored(C.byref(sh), fake, fake, None, fake, None, fake, fake, 1 << 20, None) == 1
+    assert lib.hinm_pack_vectors(C.byref(sh), fake, None, None, fake + 8, fake, fake, 1 << 20, None) == 2
+    assert lib.hinm_pack_vectors(C.byref(sh), fake, None, None, fake, fake, None, 0, None) == 4
+    assert lib.hinm_pack_vectors(C.byref(sh), fake, None, None, None, fake, fake, 1 << 20, None) == 1
+
+    def vcall(N=64, vals_v=fake, X=fake, ldx=64, ldy=64, flags=0):
+        return lib.hinm_spmm_vectors(C.byref(sh), N, vals_v, fake, None, None, X, ldx, fake, ldy, flags, None)
+    assert vcall(X=None) == 1
+    assert vcall(N=0) == 2
+    assert vcall(ldx=60) == 2
+    assert vcall(ldy=68) == 2
+    assert vcall(vals_v=fake + 8) == 2
+    assert vcall(flags=0x200) == 5           # HINM_KERNEL_SMFMAC has no meaning for a layer without the 2:4 mask
     # spmm: null X, bad N, bad ld, misaligned X, unknown flag, two kernels forced
     args = dict(N=64, vals=fake, nm=fake, vec=fake, X=fake, ldx=64, Y=fake, ldy=64, flags=0)
 
