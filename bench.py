@@ -31,6 +31,9 @@ HBM_PEAK_GBPS = 8000.0
 MFMA_DENSE_PEAK_TFLOPS = 2500.0   # fp16 / bf16 dense; useful (stored-value) flops are priced against this
 
 
+PACK_WORKLOADS = ("pack-c5", "pack-c5-ordered", "pack-c5-scored", "pack-c5-vectors")
+
+
 def workloads():
     w = {"c1": synth.c1(), "c2": synth.c2(), "c4": synth.c4(), "c5": synth.c5()}
     for c in synth.c3_cases():
@@ -79,11 +82,14 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
-    if args.workload in ("pack-c5", "pack-c5-ordered"):
+    if args.workload in PACK_WORKLOADS:
         return bench_pack(args, torch, hinm, dev)
     wl = workloads()
+    if args.workload.startswith("vectors-") and args.workload[8:] in wl:
+        return bench_vectors(args, torch, hinm, dev, wl[args.workload[8:]])
     if args.workload not in wl:
-        print("unknown workload; choose from: pack-c5 pack-c5-ordered " + " ".join(wl), file=sys.stderr)
+        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS) + " " + " ".join(wl)
+              + " vectors-<any of the latter>", file=sys.stderr)
         sys.exit(2)
     c = wl[args.workload]
     chain = args.workload == "c4"
@@ -341,24 +347,32 @@ def cpu_baseline(c, N, chain):
 
 
 def bench_pack(args, torch, hinm, dev):
+    """The offline compression step on the C5 layer: hinm_pack, or one of its variants (a tile-wise order of
+    the kept vectors, caller-given saliency scores, column-vector pruning alone)."""
     c = synth.c5()
     W = torch.from_numpy(c.weights().view(np.int16)).to(dev)
     vb, nb, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
-    vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
+    kind = args.workload[len("pack-c5"):].lstrip("-") or "plain"
+    vals = torch.empty(c.M * c.Kv if kind == "vectors" else vb // 2, dtype=torch.int16, device=dev)
     nm = torch.empty(nb, dtype=torch.uint8, device=dev)
     vec = torch.empty(cb // 4, dtype=torch.int32, device=dev)
     ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
     steps = args.steps or 10
     warmup = args.warmup or 2
-    ordered = args.workload == "pack-c5-ordered"
-    sigma = None
-    if ordered:   # a seeded random order of the input channels per tile (stands in for a search result)
-        rng = np.random.default_rng(20496)
+    sigma = rho = None
+    rng = np.random.default_rng(20496)
+    if kind == "ordered":   # a seeded random order of the input channels per tile (stands in for a search result)
         sigma = torch.from_numpy(np.stack([rng.permutation(c.K) for _ in range(c.T)]).astype(np.int32)).to(dev)
+    if kind == "scored":    # seeded non-negative scores with a wide range (stand in for second-order saliency)
+        rho = torch.from_numpy(rng.standard_normal((c.M, c.K), dtype=np.float32) ** 2).to(dev)
 
     def pack_once():
-        if ordered:
+        if kind == "ordered":
             hinm.hinm_pack_ordered(c.M, c.K, c.V, c.Kv, c.dtype, W, sigma, vals, nm, vec, ws, wb)
+        elif kind == "scored":
+            hinm.hinm_pack_scored(c.M, c.K, c.V, c.Kv, c.dtype, W, rho, None, vals, nm, vec, ws, wb)
+        elif kind == "vectors":
+            hinm.hinm_pack_vectors(c.M, c.K, c.V, c.Kv, c.dtype, W, None, None, vals, vec, ws, wb)
         else:
             hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
     for _ in range(warmup):
@@ -373,16 +387,105 @@ def bench_pack(args, torch, hinm, dev):
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / steps
     ms = e0.elapsed_time(e1) / steps
-    traffic = 2 * c.M * c.K * 2 + vb + nb + cb + 2 * wb   # W read twice, outputs, scores written + read
-    if ordered:
+    w_bytes = c.M * c.K * 2
+    traffic = 2 * w_bytes + vb + nb + cb + 2 * wb          # W read twice, outputs, scores written + read
+    if kind == "ordered":
         traffic += c.T * c.K * 4 + 2 * cb                  # the order read once, the vector index re-read and re-written
+    if kind == "scored":
+        traffic += 2 * c.M * c.K * 4 - w_bytes             # the scores read twice, W only once
+    if kind == "vectors":
+        traffic += c.M * c.Kv * 2 - vb - nb                # all surviving entries written, no NM index
+    entry = {"plain": "hinm_pack", "ordered": "hinm_pack_ordered", "scored": "hinm_pack_scored",
+             "vectors": "hinm_pack_vectors"}[kind]
     out = {"metric": "hinm_pack_gbps", "value": round(traffic / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
            "steps": steps, "warmup": warmup, "ms_per_step": round(wall * 1e3, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": c.dtype, "data": "synthetic",
-           "config": {"workload": ("hinm_pack_ordered of " if ordered else "hinm_pack of ") + c.name},
+           "config": {"workload": entry + " of " + c.name},
            "roofline": {"bound": "hbm", "achieved": round(traffic / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                         "unit": "GB/s", "frac": round(traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                         "traffic": None, "algorithmic_bytes_per_launch": traffic},
+           "cpu_baseline": None}
+    print(json.dumps(out))
+
+
+def bench_vectors(args, torch, hinm, dev, c):
+    """The product of a layer that carries the column-vector mask alone (hinm_pack_vectors, then
+    hinm_spmm_vectors per step): a dense contraction over the gathered input rows, priced against the dense
+    MFMA peak on its stored values, or against HBM when the compulsory bytes take longer."""
+    N = c.N
+    ldn = N if N == 1 else (N + 7) // 8 * 8
+    _, _, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+    W = torch.from_numpy(c.weights().view(np.int16)).to(dev)
+    vals_v = torch.empty(c.M * c.Kv, dtype=torch.int16, device=dev)
+    vec = torch.empty(cb // 4, dtype=torch.int32, device=dev)
+    ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
+    hinm.hinm_pack_vectors(c.M, c.K, c.V, c.Kv, c.dtype, W, None, None, vals_v, vec, ws, wb)
+    torch.cuda.synchronize()
+    del W, ws
+    pin = None if args.identity else torch.from_numpy(c.pi_in()).to(dev)
+    pout = None if args.identity else torch.from_numpy(c.pi_out()).to(dev)
+    Xh = np.zeros((c.K, ldn), dtype=np.uint16)
+    Xh[:, :N] = c.activations()
+    X0 = torch.from_numpy(Xh.view(np.int16)).to(dev)
+    per_set = c.M * c.Kv * 2 + cb + (c.K + c.M) * ldn * 2
+    n_sets = args.sets if args.sets else max(2, min(64, int(np.ceil(600e6 / per_set))))
+    sets = [(vals_v if i == 0 else vals_v.clone(), vec if i == 0 else vec.clone(), X0 if i == 0 else X0.clone(),
+             torch.zeros((c.M, ldn), dtype=torch.int16, device=dev)) for i in range(n_sets)]
+
+    def step(i):
+        v, ve, X, Y = sets[i % n_sets]
+        hinm.hinm_spmm_vectors(c.M, c.K, c.V, c.Kv, c.dtype, N, v, ve, pin, pout, X, ldn, Y, ldn, 0)
+
+    step(0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(3):
+        step(i)
+    torch.cuda.synchronize()
+    est = (time.perf_counter() - t0) / 3
+    steps = args.steps if args.steps is not None else int(min(2000, max(10, 1.0 / max(est, 1e-6))))
+    warmup = args.warmup if args.warmup is not None else max(2, steps // 10)
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(steps):
+                step(i)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    graph.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    kernel_ms = ev0.elapsed_time(ev1) / steps
+    flops = 2.0 * c.M * c.Kv * N
+    bytes_step = c.M * c.Kv * 2 + cb + (c.K + c.M) * 4 + c.K * N * 2 + c.M * N * 2
+    if bytes_step / HBM_PEAK_GBPS / 1e9 >= flops / MFMA_DENSE_PEAK_TFLOPS / 1e12:
+        ach = bytes_step / (kernel_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None}
+    else:
+        ach = flops / (kernel_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / MFMA_DENSE_PEAK_TFLOPS, 4), "traffic": None}
+    roofline.update({"kernel": "spmm_vectors_kernel", "kernel_ms_avg": round(kernel_ms, 6),
+                     "algorithmic_bytes_per_launch": bytes_step, "stored_value_flops_per_launch": flops})
+    out = {"metric": "hinm_spmm_dense_equiv_tflops", "value": round(2.0 * c.M * c.K * N / (ms_per_step * 1e-3) / 1e12, 3),
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": c.dtype, "data": "synthetic",
+           "config": {"workload": "vector-pruned only (no 2:4 step): " + c.name, "M": c.M, "K": c.K, "V": c.V,
+                      "Kv": c.Kv, "N": N, "permutation": "identity" if args.identity else "seeded random pi_in/pi_out",
+                      "buffer_sets_rotated": n_sets, "entry_point": "hinm_spmm_vectors",
+                      "launch": "one HIP graph of K steps"},
+           "stored_value_tflops": round(flops / (kernel_ms * 1e-3) / 1e12, 3), "roofline": roofline,
            "cpu_baseline": None}
     print(json.dumps(out))
 

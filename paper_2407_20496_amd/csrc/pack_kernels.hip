@@ -374,17 +374,23 @@ __global__ __launch_bounds__(256) void scatter_kernel(const uint16_t* __restrict
 constexpr int kEmitRowMaxK = 32 * 1024;
 constexpr int kEmitRowScoredMaxK = 16 * 1024;
 
+template <int THREADS>
 __device__ __forceinline__ void stage_row(uint16_t* row, const uint16_t* __restrict__ wr, int K, bool vec8) {
   if (vec8) {  // K % 8 == 0 and the source 16-byte aligned
-    for (int i = threadIdx.x; i < K / 8; i += kEmitThreads)
+    for (int i = threadIdx.x; i < K / 8; i += THREADS)
       reinterpret_cast<uint4*>(row)[i] = reinterpret_cast<const uint4*>(wr)[i];
   } else {
-    for (int i = threadIdx.x; i < K; i += kEmitThreads) row[i] = wr[i];
+    for (int i = threadIdx.x; i < K; i += THREADS) row[i] = wr[i];
   }
 }
 
+// With scores a row needs three times the LDS, so fewer workgroups fit a compute unit: they are made
+// of 1024 threads then, to keep the unit's memory pipeline full.
 template <bool SCORED>
-__global__ __launch_bounds__(kEmitThreads) void emit_rows_kernel(const uint16_t* __restrict__ W,
+constexpr int kEmitRowThreads = SCORED ? 1024 : kEmitThreads;
+
+template <bool SCORED>
+__global__ __launch_bounds__(kEmitRowThreads<SCORED>) void emit_rows_kernel(const uint16_t* __restrict__ W,
                                                                  const float* __restrict__ rho,
                                                                  const int32_t* __restrict__ vec_idx,
                                                                  uint16_t* __restrict__ vals,
@@ -394,21 +400,22 @@ __global__ __launch_bounds__(kEmitThreads) void emit_rows_kernel(const uint16_t*
   const int K8 = (K + 7) / 8 * 8;
   float* score_row = reinterpret_cast<float*>(emit_lds);                     // K floats, only when SCORED
   uint16_t* row = reinterpret_cast<uint16_t*>(emit_lds + (SCORED ? (size_t)K8 * 4 : 0));  // K elements
+  constexpr int THREADS = kEmitRowThreads<SCORED>;
   const int r = blockIdx.x;
   const int t = r / V;
-  stage_row(row, W + (size_t)r * K, K, vec8);
+  stage_row<THREADS>(row, W + (size_t)r * K, K, vec8);
   if constexpr (SCORED) {
     const float* rr = rho + (size_t)r * K;
     if (rho_vec4) {  // K % 4 == 0 and rho 16-byte aligned
-      for (int i = threadIdx.x; i < K / 4; i += kEmitThreads)
+      for (int i = threadIdx.x; i < K / 4; i += THREADS)
         reinterpret_cast<float4*>(score_row)[i] = reinterpret_cast<const float4*>(rr)[i];
     } else {
-      for (int i = threadIdx.x; i < K; i += kEmitThreads) score_row[i] = rr[i];
+      for (int i = threadIdx.x; i < K; i += THREADS) score_row[i] = rr[i];
     }
   }
   __syncthreads();
   const int bytes_per_row = Kv / 8;
-  for (int b = threadIdx.x; b < bytes_per_row; b += kEmitThreads)
+  for (int b = threadIdx.x; b < bytes_per_row; b += THREADS)
     emit_byte<SCORED>(
         vec_idx + (size_t)t * Kv + 8 * b, [&](int c) { return row[c]; }, [&](int c) { return score_row[c]; },
         vals + (size_t)r * (Kv / 2) + 4 * b, nm_idx + (size_t)r * bytes_per_row + b);
@@ -421,7 +428,7 @@ __global__ __launch_bounds__(kEmitThreads) void gather_rows_kernel(const uint16_
   extern __shared__ __attribute__((aligned(16))) uint8_t emit_lds[];
   uint16_t* row = reinterpret_cast<uint16_t*>(emit_lds);
   const int r = blockIdx.x;
-  stage_row(row, W + (size_t)r * K, K, vec8);
+  stage_row<kEmitThreads>(row, W + (size_t)r * K, K, vec8);
   __syncthreads();
   const int32_t* vt = vec_idx + (size_t)(r / V) * Kv;
   for (int b = threadIdx.x; b < Kv / 8; b += kEmitThreads) {
@@ -541,7 +548,7 @@ hipError_t launch_pack(const PackArgs& a, hipStream_t stream) {
       const size_t lds_bytes = 3 * row_bytes;
       e = allow_lds(emit_rows_kernel<true>, lds_bytes);
       if (e != hipSuccess) return e;
-      emit_rows_kernel<true><<<(unsigned)s.M, kEmitThreads, lds_bytes, stream>>>(Wb, a.rho, a.vec_idx, vals, a.nm_idx,
+      emit_rows_kernel<true><<<(unsigned)s.M, kEmitRowThreads<true>, lds_bytes, stream>>>(Wb, a.rho, a.vec_idx, vals, a.nm_idx,
                                                                                  s.K, s.V, s.Kv, vec8, rho_vec4);
     } else {
       emit_kernel<true><<<flat_blocks, kEmitThreads, 0, stream>>>(Wb, a.rho, a.vec_idx, vals, a.nm_idx, s.M, s.K, s.V,
