@@ -10,7 +10,14 @@ the offline compression step of the method; it is timed by `--workload pack-c5`.
 Consecutive steps rotate over enough independent copies of (packed W, X, Y)
 to exceed the 256 MB Infinity Cache, so the traffic really comes from HBM.
 
-Prints ONE JSON line (see the design doc for the field definitions).
+Other workloads: `pack-c5[-ordered|-scored|-vectors]` (the offline compression step and its variants),
+`vectors-<case>` (the product of a layer that carries the column-vector mask alone), `sweep-bert` /
+`sweep-resnet` (every layer of a model block at several vector sizes and vector sparsities, with and
+without channel orders, beside the dense GEMM).
+
+Prints ONE JSON line: metric / value / unit (dense-equivalent TFLOP/s of the whole job), ms_per_step, the
+workload in `config`, `roofline` (algorithmic bytes or stored-value flops per launch over the measured kernel
+time, against the HBM or MFMA peak) and `cpu_baseline` (the CPU oracle timed on a bounded sample).
 """
 from __future__ import annotations
 
@@ -32,6 +39,9 @@ MFMA_DENSE_PEAK_TFLOPS = 2500.0   # fp16 / bf16 dense; useful (stored-value) flo
 
 
 PACK_WORKLOADS = ("pack-c5", "pack-c5-ordered", "pack-c5-scored", "pack-c5-vectors")
+
+
+SWEEP_WORKLOADS = ("sweep-bert", "sweep-resnet")
 
 
 def workloads():
@@ -84,11 +94,13 @@ def main():
 
     if args.workload in PACK_WORKLOADS:
         return bench_pack(args, torch, hinm, dev)
+    if args.workload in SWEEP_WORKLOADS:
+        return bench_sweep(args, torch, hinm, dev)
     wl = workloads()
     if args.workload.startswith("vectors-") and args.workload[8:] in wl:
         return bench_vectors(args, torch, hinm, dev, wl[args.workload[8:]])
     if args.workload not in wl:
-        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS) + " " + " ".join(wl)
+        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS + SWEEP_WORKLOADS) + " " + " ".join(wl)
               + " vectors-<any of the latter>", file=sys.stderr)
         sys.exit(2)
     c = wl[args.workload]
@@ -487,6 +499,111 @@ def bench_vectors(args, torch, hinm, dev, c):
                       "launch": "one HIP graph of K steps"},
            "stored_value_tflops": round(flops / (kernel_ms * 1e-3) / 1e12, 3), "roofline": roofline,
            "cpu_baseline": None}
+    print(json.dumps(out))
+
+
+def bench_sweep(args, torch, hinm, dev):
+    """Section 5.3 (latency figure): the same layers at several vector sizes and vector sparsities, with seeded
+    random channel orders and with identity orders, beside the dense GEMM of the unpruned layer.  One JSON
+    line; `value` is the dense-equivalent rate of the whole sweep with channel orders, `table` holds one row
+    per (V, vector sparsity): microseconds summed over the layers."""
+    layers = synth.sweep_layers(args.workload)
+    bert = args.workload == "sweep-bert"
+    v_list = (32, 64, 128) if bert else (32,)
+    keep_list = ((2, "50"), (4, "75"), (8, "87.5"))         # Kv = K / keep -> total sparsity 75 / 87.5 / 93.75 %
+    dtype = "f16"
+    tdt = torch.float16
+    steps = args.steps or 200
+
+    def graph_time_us(launch, n_sets):
+        for i in range(3):
+            launch(i)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for i in range(steps):
+                    launch(i)
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / steps
+
+    table, dense_us = [], {}
+    flops_total, time_total = 0.0, 0.0
+    for li, (name, M, K, N) in enumerate(layers):
+        ldn = (N + 7) // 8 * 8
+        Wb = synth.gaussian_bits((M, K), 0.02, dtype, synth.seed_for(5, 0) + 1000 * li)
+        Xh = np.zeros((K, ldn), dtype=np.uint16)
+        Xh[:, :N] = synth.gaussian_bits((K, N), 1.0, dtype, synth.seed_for(5, 1) + 1000 * li)
+        Wd = torch.from_numpy(Wb.view(np.int16)).to(dev)
+        n_sets = max(2, min(32, int(np.ceil(600e6 / ((K + M) * ldn * 2)))))
+        Xs = [torch.from_numpy(Xh.view(np.int16)).to(dev) for _ in range(n_sets)]
+        Ys = [torch.zeros((M, ldn), dtype=torch.int16, device=dev) for _ in range(n_sets)]
+        Wt = Wd.view(tdt).reshape(M, K)
+        Yd = [torch.empty((M, N), dtype=tdt, device=dev) for _ in range(n_sets)]
+        Xt = [x.view(tdt).reshape(K, ldn)[:, :N] for x in Xs]
+        dense_us[name] = graph_time_us(lambda i: torch.matmul(Wt, Xt[i % n_sets], out=Yd[i % n_sets]), n_sets)
+        del Yd
+        pin = torch.from_numpy(synth.permutation(K, synth.seed_for(5, 2) + 1000 * li)).to(dev)
+        pout = torch.from_numpy(synth.permutation(M, synth.seed_for(5, 3) + 1000 * li)).to(dev)
+        for V in v_list:
+            if M % V:
+                continue
+            for keep, label in keep_list:
+                Kv = K // keep
+                vb, nb, cb, wb = hinm.hinm_pack_sizes(M, K, V, Kv, dtype)
+                vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
+                nm = torch.empty(nb, dtype=torch.uint8, device=dev)
+                vec = torch.empty(cb // 4, dtype=torch.int32, device=dev)
+                ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
+                hinm.hinm_pack(M, K, V, Kv, dtype, Wd, vals, nm, vec, ws, wb)
+                pbytes = hinm.hinm_prepare_sizes(M, K, V, Kv, dtype)
+                wsb = hinm.hinm_spmm_prepared_workspace(M, K, V, Kv, dtype, N)
+                wsp = torch.zeros(max(wsb, 1), dtype=torch.uint8, device=dev)
+                us = {}
+                for ident in (False, True):
+                    preps = []
+                    for _ in range(n_sets):
+                        pr = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+                        hinm.hinm_prepare(M, K, V, Kv, dtype, vals, nm, vec, None if ident else pin,
+                                          None if ident else pout, pr, pbytes)
+                        preps.append(pr)
+                    torch.cuda.synchronize()
+                    us[ident] = graph_time_us(
+                        lambda i: hinm.hinm_spmm_prepared(M, K, V, Kv, dtype, N, preps[i % n_sets], Xs[i % n_sets], ldn,
+                                                          Ys[i % n_sets], ldn, 0, wsp if wsb else None, wsb), n_sets)
+                    del preps
+                table.append({"layer": name, "M": M, "K": K, "N": N, "V": V, "vector_sparsity": label, "Kv": Kv,
+                              "us": round(us[False], 2), "us_identity": round(us[True], 2),
+                              "us_dense_gemm": round(dense_us[name], 2)})
+                flops_total += 2.0 * M * K * N
+                time_total += us[False] * 1e-6
+    # one row per (V, vector sparsity): all layers of the model block summed
+    summary = []
+    for V in v_list:
+        for _, label in keep_list:
+            rows = [r for r in table if r["V"] == V and r["vector_sparsity"] == label]
+            if not rows:
+                continue
+            t, ti, td = (sum(r[k] for r in rows) for k in ("us", "us_identity", "us_dense_gemm"))
+            summary.append({"V": V, "vector_sparsity": label, "layers": len(rows), "us": round(t, 1),
+                            "us_identity": round(ti, 1), "permutation_overhead": round(t / ti - 1.0, 4),
+                            "us_dense_gemm": round(td, 1), "speedup_vs_dense": round(td / t, 3)})
+    out = {"metric": "hinm_spmm_dense_equiv_tflops", "value": round(flops_total / time_total / 1e12, 3),
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": round(time_total * 1e3, 6),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+           "config": {"workload": ("BERT-base encoder layer, 8 x 512 tokens" if bert else
+                                   "ResNet 3x3 convolutions as GEMMs, 8 images") + ": every layer x V x vector sparsity",
+                      "entry_point": "hinm_spmm_prepared", "launch": "one HIP graph of K steps per case"},
+           "summary": summary, "table": table, "roofline": None, "cpu_baseline": None}
     print(json.dumps(out))
 
 

@@ -148,3 +148,15 @@ def small_case(M: int, K: int, V: int, Kv: int, N: int, dtype: str, salt: int) -
     """Free-form case for unit tests (config id 9 keeps seeds apart from the
     five named workloads)."""
     return Case(f"unit {M}x{K} V{V} Kv{Kv} N{N} {dtype}", 9, M, K, V, Kv, N, dtype, seed_salt=salt)
+
+
+def sweep_layers(which):
+    """GEMM shapes (name, M, K, N) behind the latency figure of Section 5.3 (BERT-base, all linear layers of one
+    encoder layer at 8 x 512 tokens) and behind the V = 32 convolution experiments of Section 5.1.1 (3x3
+    convolutions of the four ResNet stages as GEMMs, M = output channels, K = 9 x input channels, N = 8 images x
+    output pixels).  Weights and activations are seeded synthetic tensors of these shapes."""
+    if which == "sweep-bert":
+        return [("attention q", 768, 768, 4096), ("attention k", 768, 768, 4096), ("attention v", 768, 768, 4096),
+                ("attention out", 768, 768, 4096), ("ffn up", 3072, 768, 4096), ("ffn down", 768, 3072, 4096)]
+    return [("stage1 3x3 64ch 56x56", 64, 576, 8 * 56 * 56), ("stage2 3x3 128ch 28x28", 128, 1152, 8 * 28 * 28),
+            ("stage3 3x3 256ch 14x14", 256, 2304, 8 * 14 * 14), ("stage4 3x3 512ch 7x7", 512, 4608, 8 * 7 * 7)]

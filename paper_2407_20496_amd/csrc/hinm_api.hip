@@ -295,7 +295,7 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
     e = launch_spmm_skinny_prepared(a, stream);
   } else {
     if (N == 1 || ldx % 8 != 0 || ldy % 8 != 0) return HINM_ERR_UNSUPPORTED;
-    const bool panel = (a.tile_variant == 15) || (a.tile_variant == 0 && spmm_panel_prepared_supported(a));
+    const bool panel = (a.tile_variant == 15) || (a.tile_variant == 0 && spmm_panel_prepared_preferred(a));
     if (panel && !spmm_panel_prepared_supported(a)) return HINM_ERR_UNSUPPORTED;
     e = panel ? launch_spmm_panel_prepared(a, stream) : launch_spmm_tile_prepared(a, stream);
   }

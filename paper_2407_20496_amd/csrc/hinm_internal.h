@@ -115,6 +115,7 @@ struct PreparedArgs {
 hipError_t launch_spmm_tile_prepared(const PreparedArgs& a, hipStream_t stream);
 // few input channels (a 64-column panel of X with all K rows fits in LDS): many tiles per workgroup
 bool spmm_panel_prepared_supported(const PreparedArgs& a);
+bool spmm_panel_prepared_preferred(const PreparedArgs& a);  // supported and faster than the tile kernel
 hipError_t launch_spmm_panel_prepared(const PreparedArgs& a, hipStream_t stream);
 // few columns (N <= 32): whole-tile workgroups, kept columns split over workgroups
 size_t skinny_prepared_workspace_bytes(const hinm_shape& s, int N);

@@ -381,10 +381,14 @@ inline int choose_variant(const PreparedArgs& a) {
   const PreparedLayout L = prepared_layout(a.s);
   const int64_t wide_blocks = (int64_t)L.T * ((a.N + 511) / 512);
   if (a.N >= 1024 && wide_blocks >= 256) return 3;  // 512 columns, 64-column stages, 2 deep
-  if (L.S <= 8) return 8;                           // 256 columns, 32-column stages, 2 deep
+  // 128-row tiles with a short k loop: the wide block still pays with half as many workgroups as units
+  if (a.N >= 1024 && L.RB == 4 && L.S <= 8 && wide_blocks >= 128) return 3;
+  const int64_t blocks = (int64_t)L.T * ((a.N + 255) / 256);
+  // short k loops with several workgroups per compute unit: 32-column stages, 2 deep (the workgroups
+  // cover each other's start-up and epilogue); with fewer workgroups the larger stages below win
+  if (L.S <= 8 && blocks > 512) return 8;
   // At most one workgroup per compute unit: every stage then waits one full memory round trip, and
   // 128-column stages halve the number of round trips.
-  const int64_t blocks = (int64_t)L.T * ((a.N + 255) / 256);
   if (L.RB <= 2 && L.S % 2 == 0 && blocks <= 256) return 10;
   return 1;                                         // 256 columns, 64-column stages, 2 deep
 }
