@@ -83,7 +83,8 @@ enum {
   HINM_KERNEL_SMFMAC = 0x200u,    /* a sparse-MFMA kernel: 32x32 tiles (V in {32,64,96,128}, Kv % 32 == 0,
                                      ld % 8 == 0) or else the 16-column form (V % 16 == 0) */
   HINM_KERNEL_GEMV = 0x400u,      /* 16-column sparse-MFMA form with k split over the waves; N <= 16, V % 16 == 0 */
-  /* hinm_spmm_prepared only, tuning aid: bits 16..19 pin one kernel configuration (0 = by shape) */
+  /* hinm_spmm_prepared and hinm_spmm_vectors only, tuning aid: bits 16..19 pin one kernel configuration
+   * (0 = by shape); a configuration that does not fit the shape returns HINM_ERR_UNSUPPORTED */
   HINM_VARIANT_SHIFT = 16,
   HINM_VARIANT_MASK = 0xF0000u
 };
@@ -166,9 +167,10 @@ hinm_status hinm_spmm(const hinm_shape* shape, int32_t N,
  *     Y[pi_out[r]][n] = sum_j vals_v[r][j] * X[pi_in[vec_idx[r / V][j]]][n],
  * vals_v and vec_idx as written by hinm_pack_vectors (vals_v 16-byte aligned).  fp32 accumulation,
  * rounding, pi_in / pi_out, ldx / ldy and alignment rules as for hinm_spmm.  flags: HINM_EPI_RELU,
- * HINM_OUT_F32, HINM_KERNEL_REFERENCE (one thread per output element); anything else returns
- * HINM_ERR_UNSUPPORTED.  V in {32, 64, 96, 128} runs on the dense MFMA, other shapes on the
- * plain kernel.  Needs no workspace. */
+ * HINM_OUT_F32, HINM_KERNEL_REFERENCE (one thread per output element), the variant bits (1 =
+ * register-staged tile kernel, 2 / 3 = direct-to-LDS tile kernel with 256- / 512-column blocks,
+ * which need Kv % 64 == 0); anything else returns HINM_ERR_UNSUPPORTED.  V in {32, 64, 96, 128}
+ * with N > 1 runs on the dense MFMA, other shapes on the plain kernel.  Needs no workspace. */
 hinm_status hinm_spmm_vectors(const hinm_shape* shape, int32_t N,
                               const void* vals_v, const int32_t* vec_idx,
                               const int32_t* pi_in, const int32_t* pi_out,

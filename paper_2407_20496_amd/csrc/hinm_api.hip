@@ -147,10 +147,14 @@ hinm_status hinm_spmm_vectors(const hinm_shape* shape, int32_t N, const void* va
   if (N <= 0 || ldx < N || ldy < N) return HINM_ERR_SHAPE;
   if (N > 1 && (ldx % 8 != 0 || ldy % 8 != 0)) return HINM_ERR_SHAPE;
   if (!aligned(vals_v, 16) || !aligned(X, 16) || !aligned(Y, 16)) return HINM_ERR_SHAPE;
-  if (flags & ~(uint32_t)(HINM_EPI_RELU | HINM_OUT_F32 | HINM_KERNEL_REFERENCE)) return HINM_ERR_UNSUPPORTED;
+  if (flags & ~(uint32_t)(HINM_EPI_RELU | HINM_OUT_F32 | HINM_KERNEL_REFERENCE | HINM_VARIANT_MASK))
+    return HINM_ERR_UNSUPPORTED;
+  const int variant = (int)((flags & HINM_VARIANT_MASK) >> HINM_VARIANT_SHIFT);
+  if (variant && (flags & HINM_KERNEL_REFERENCE)) return HINM_ERR_UNSUPPORTED;
   const VectorsArgs a{*shape, N, vals_v, vec_idx, pi_in, pi_out, X, ldx, Y, ldy,
-                      (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0};
+                      (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0, variant};
   hipError_t e;
+  if (variant && !spmm_vectors_mfma_supported(a)) return HINM_ERR_UNSUPPORTED;  // a pinned kernel must fit the shape
   if (!(flags & HINM_KERNEL_REFERENCE) && spmm_vectors_mfma_supported(a))
     e = launch_spmm_vectors_mfma(a, static_cast<hipStream_t>(stream));
   else

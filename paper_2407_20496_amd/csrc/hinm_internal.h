@@ -87,9 +87,12 @@ struct VectorsArgs {
   int64_t ldy;
   bool relu;
   bool out_f32;
+  int variant;  // 0 = choose by shape; 1 = register-staged, 2 / 3 = direct-to-LDS with 256 / 512 columns
 };
-// Dense-MFMA tile kernel: V in {32, 64, 96, 128}, ldx % 8 == 0, ldy % 8 == 0.
+// Dense-MFMA tile kernels: V in {32, 64, 96, 128}, ldx % 8 == 0, ldy % 8 == 0; the direct-to-LDS ones
+// also need Kv % 64 == 0.
 bool spmm_vectors_mfma_supported(const VectorsArgs& a);
+int spmm_vectors_variant(const VectorsArgs& a);
 hipError_t launch_spmm_vectors_mfma(const VectorsArgs& a, hipStream_t stream);
 hipError_t launch_spmm_vectors_plain(const VectorsArgs& a, hipStream_t stream);
 

@@ -83,6 +83,8 @@ def test_null_and_workspace_errors_are_reported_before_any_launch():
     assert vcall(ldx=60) == 2
     assert vcall(ldy=68) == 2
     assert vcall(vals_v=fake + 8) == 2
+    assert vcall(flags=2 << 16) == 5     # V = 16 here: no tile kernel to pin
+    assert vcall(flags=0x100 | 1 << 16) == 5
     assert vcall(flags=0x200) == 5           # HINM_KERNEL_SMFMAC has no meaning for a layer without the 2:4 mask
     # spmm: null X, bad N, bad ld, misaligned X, unknown flag, two kernels forced
     args = dict(N=64, vals=fake, nm=fake, vec=fake, X=fake, ldx=64, Y=fake, ldy=64, flags=0)

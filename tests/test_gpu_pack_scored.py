@@ -163,9 +163,42 @@ def test_spmm_vectors_matches_the_oracle(M, K, V, Kv, N, dtype, flags):
         # 16-bit outputs must be the correctly rounded accumulators
         got = gu.gpu_spmm_vectors(pv, Xb, pin, pout, flags=flags)
         assert np.array_equal(got, orc.round_to_storage(got32, dtype))
+    # every tile kernel that fits the shape, pinned through the variant bits
+    if V % 32 == 0 and N > 1 and not flags & 0x100:
+        for variant in (1, 2, 3):
+            if variant >= 2 and Kv % 64:
+                continue
+            g = gu.gpu_spmm_vectors(pv, Xb, pin, pout, flags=(flags & 1) | 2 | variant << 16)
+            gu.check_close(g.astype(np.float64), want, what=f"vector-only product, kernel variant {variant}")
     # identity orders reduce to W_v @ X
     got_id = gu.gpu_spmm_vectors(pv, Xb, None, None, flags=2 | (flags & 0x100)).astype(np.float64)
     gu.check_close(got_id, orc.product(Wv, Xb, dtype, None, None, acc=np.float64), what="identity orders")
+
+
+@pytest.mark.parametrize("M,K,V,Kv,N,dtype", [
+    (4096, 256, 32, 128, 1030, "bf16"),     # 512-column blocks, ragged last block, 32-row tiles
+    (4096, 512, 64, 256, 2048, "f16"),      # 512-column blocks, 64-row tiles
+    (3072, 640, 96, 320, 1536, "bf16"),     # 96-row tiles
+    (2048, 1024, 128, 64, 4096, "f16"),     # a single stage
+])
+def test_spmm_vectors_wide_blocks_sampled_outputs(M, K, V, Kv, N, dtype):
+    from tests import gpu_util as gu
+    c = synth.small_case(M, K, V, Kv, N, dtype, 57)
+    Wb, Xb = c.weights(), c.activations()
+    sigma = _sigma(M // V, K, 58)
+    pv = gu.gpu_pack_vectors(Wb, dtype, V, Kv, sigma=sigma)
+    o_vals_v, o_vec = orc.pack_vectors(Wb, dtype, V, Kv, sigma=sigma)
+    assert np.array_equal(pv.host()[0], o_vals_v)
+    Wv = orc.unpack_vectors(o_vals_v, o_vec, M, K, V)
+    pin, pout = c.pi_in(), c.pi_out()
+    got = gu.gpu_spmm_vectors(pv, Xb, pin, pout, flags=2).astype(np.float64)
+    rng = np.random.default_rng(59)
+    rows = rng.choice(M, 64, replace=False)
+    cols = np.unique(np.concatenate([rng.choice(N, 96, replace=False), [0, 511, 512, N - 1]]))
+    want = orc.product_entries(Wv, Xb, dtype, pin, pout, rows, cols)
+    gu.check_close(got[np.asarray(pout)[rows]][:, cols], want, what="vector-only product, wide blocks")
+    got16 = gu.gpu_spmm_vectors(pv, Xb, pin, pout, flags=0)
+    assert np.array_equal(got16, orc.round_to_storage(got.astype(np.float32), dtype))
 
 
 def test_spmm_vectors_c2_sampled_outputs():
