@@ -1,0 +1,121 @@
+"""CPU oracle for the tile-wise input-channel permutation search of gyro-permutation.
+
+TEST INFRASTRUCTURE ONLY.  Slow, plain definition of what the HIP library's search computes; it
+shares no code with the HIP path and must never be imported by it.
+
+What it follows (arXiv 2407.20496):
+  * Section 4.1, Eq. 3: after column-vector pruning, the kept column vectors of every tile are
+    re-arranged so that the 2:4 step retains as much saliency as possible; every four consecutive
+    kept vectors form one partition (one 2:4 group per row).
+  * Section 4.2: one iteration = sampling (here exactly one column vector per partition, so the
+    clustering phase is bypassed), the cost of placing sample j into partition i (Eq. 4: the
+    saliency that the 2:4 step would prune in partition i's three remaining vectors plus sample j),
+    and an assignment of samples to partitions that minimises the total cost (the paper names the
+    Hungarian algorithm; any exact solver of the linear assignment problem reaches the same minimum).
+
+Readings where the paper is silent (repeated in the design notes): which member of a partition is
+sampled is an input (the caller draws it); a sample moves into the slot its destination partition
+vacated; the cost is the plain sum of the pruned saliencies (not total minus retained), per row the
+two smallest of the four values added exactly, rows accumulated in binary64 in ascending order;
+saliency = caller-given rho (float32) or |w|; several assignments may reach the minimum, any of
+them is a correct result, and the number of iterations is the caller's.
+
+Pins: tests/test_oracle_gyro.py (brute force over all assignments, the hand-derived example in
+tests/golden/hand_example_icp.txt, cost of the identity assignment = current pruned saliency,
+total cost of an assignment = pruned saliency after the move, the objective never increases, and
+the final arrangement fed to the packing oracle prunes exactly the final objective).
+"""
+from __future__ import annotations
+
+from typing import Optional, Tuple
+
+import numpy as np
+from scipy.optimize import linear_sum_assignment
+
+from oracle import hinm_oracle as orc
+
+
+def kept_saliency(W_bits: np.ndarray, dtype: str, rho: Optional[np.ndarray], V: int, vec_idx_t: np.ndarray,
+                  t: int) -> np.ndarray:
+    """Saliency of tile t's entries in the columns vec_idx_t, float64 [V, len(vec_idx_t)]: the
+    caller's rho, or |w|."""
+    rows = slice(t * V, (t + 1) * V)
+    if rho is not None:
+        return np.asarray(rho)[rows][:, vec_idx_t].astype(np.float64)
+    return np.abs(orc.decode(np.asarray(W_bits)[rows][:, vec_idx_t], dtype))
+
+
+def pruned_saliency(S: np.ndarray) -> float:
+    """S: float64 [V, Kv], columns in arrangement order.  What the 2:4 step prunes: per row and group of
+    four the two smallest values; groups in ascending order, inside a group rows in ascending order."""
+    V, Kv = S.shape
+    total = 0.0
+    for g in range(Kv // 4):
+        acc = 0.0
+        for r in range(V):
+            four = np.sort(S[r, 4 * g:4 * g + 4])
+            acc = acc + (four[0] + four[1])
+        total = total + acc
+    return total
+
+
+def icp_cost(S: np.ndarray, sampled: np.ndarray) -> np.ndarray:
+    """Eq. 4 for one tile.  S: float64 [V, Kv] in arrangement order; sampled[i] in 0..3 = the member of
+    partition i that is taken out.  cost[i, j] = saliency pruned in partition i when its vacated slot
+    holds sample j: float64 [P, P]."""
+    V, Kv = S.shape
+    P = Kv // 4
+    cost = np.zeros((P, P), dtype=np.float64)
+    for i in range(P):
+        rem = [4 * i + m for m in range(4) if m != int(sampled[i])]
+        for j in range(P):
+            col = 4 * j + int(sampled[j])
+            acc = 0.0
+            for r in range(V):   # sequential on purpose: pins the rounding order
+                four = np.sort(np.array([S[r, rem[0]], S[r, rem[1]], S[r, rem[2]], S[r, col]]))
+                acc = acc + (four[0] + four[1])
+            cost[i, j] = acc
+    return cost
+
+
+def icp_assign(cost: np.ndarray) -> np.ndarray:
+    """assign[i] = the sample placed into partition i, minimising sum_i cost[i, assign[i]]."""
+    rows, cols = linear_sum_assignment(cost)
+    out = np.empty(cost.shape[0], dtype=np.int64)
+    out[rows] = cols
+    return out
+
+
+def assignment_cost(cost: np.ndarray, assign: np.ndarray) -> float:
+    """Total cost of an assignment, partitions added in ascending order."""
+    total = 0.0
+    for i in range(cost.shape[0]):
+        total = total + cost[i, int(assign[i])]
+    return total
+
+
+def icp_apply(arrangement: np.ndarray, sampled: np.ndarray, assign: np.ndarray) -> np.ndarray:
+    """Moves sample assign[i] into the slot partition i vacated.  arrangement: the tile's kept columns
+    in order [Kv]; returns the new order."""
+    out = np.array(arrangement, copy=True)
+    for i in range(len(sampled)):
+        j = int(assign[i])
+        out[4 * i + int(sampled[i])] = arrangement[4 * j + int(sampled[j])]
+    return out
+
+
+def icp_search(W_bits: np.ndarray, dtype: str, rho: Optional[np.ndarray], V: int, vec_idx: np.ndarray,
+               samples: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """samples: [iters, T, Kv/4] members 0..3.  Returns (vec_idx after all iterations [T, Kv],
+    objective [iters, T] = saliency pruned by the 2:4 step after each iteration)."""
+    vec = np.array(vec_idx, copy=True)
+    iters, T, P = samples.shape
+    objective = np.zeros((iters, T), dtype=np.float64)
+    for it in range(iters):
+        for t in range(T):
+            S = kept_saliency(W_bits, dtype, rho, V, vec[t], t)
+            cost = icp_cost(S, samples[it, t])
+            assign = icp_assign(cost)
+            objective[it, t] = assignment_cost(cost, assign)
+            vec[t] = icp_apply(vec[t], samples[it, t], assign)
+    return vec, objective

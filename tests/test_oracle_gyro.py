@@ -1,0 +1,88 @@
+"""Pins for the oracle of the tile-wise input-channel permutation search (no GPU)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import hinm_synth as synth
+from oracle import gyro_oracle as gyro
+from oracle import hinm_oracle as orc
+from tests.conftest import load_golden
+
+
+def test_hand_example():
+    ex = load_golden("hand_example_icp.txt")
+    S = ex["rho"].astype(np.float64)
+    sampled = ex["samples"].reshape(-1)
+    cost = gyro.icp_cost(S, sampled)
+    assert cost.tolist() == ex["cost"].astype(np.float64).tolist()
+    assign = gyro.icp_assign(cost)
+    assert assign.tolist() == ex["assign"].reshape(-1).tolist()
+    assert gyro.assignment_cost(cost, assign) == float(ex["objective"][0, 0])
+    after = gyro.icp_apply(ex["vec_idx"].reshape(-1), sampled, assign)
+    assert after.tolist() == ex["vec_idx_after"].reshape(-1).tolist()
+    assert gyro.pruned_saliency(S[:, after]) == float(ex["objective"][0, 0])
+    # the same through the search on a weight matrix whose magnitudes are these scores
+    Wb = synth.to_bits((ex["rho"] * np.array([[1], [-1]])).astype(np.float32), "f16")
+    vec, obj = gyro.icp_search(Wb, "f16", None, 2, ex["vec_idx"], sampled.reshape(1, 1, 2))
+    assert vec.tolist() == ex["vec_idx_after"].tolist() and obj.tolist() == [[21.0]]
+
+
+def _integer_tile(V, Kv, seed):
+    rng = np.random.default_rng(seed)
+    return rng.integers(0, 20, size=(V, Kv)).astype(np.float64), rng.integers(0, 4, size=Kv // 4)
+
+
+@pytest.mark.parametrize("P", [2, 3, 5, 6])
+def test_assignment_is_the_brute_force_minimum(P):
+    S, sampled = _integer_tile(3, 4 * P, 70 + P)
+    cost = gyro.icp_cost(S, sampled)
+    best = min(sum(cost[i, perm[i]] for i in range(P)) for perm in itertools.permutations(range(P)))
+    assign = gyro.icp_assign(cost)
+    assert sorted(assign.tolist()) == list(range(P))
+    assert gyro.assignment_cost(cost, assign) == best
+
+
+def test_cost_is_the_pruned_saliency_of_the_arrangement_it_describes():
+    # integer scores: every sum is exact, so the identities hold bit for bit
+    S, sampled = _integer_tile(5, 24, 81)
+    P = 6
+    cost = gyro.icp_cost(S, sampled)
+    arrangement = np.arange(24)
+    ident = np.arange(P)
+    assert gyro.assignment_cost(cost, ident) == gyro.pruned_saliency(S)          # nothing moves
+    for perm in ([1, 0, 2, 3, 4, 5], [5, 4, 3, 2, 1, 0], [2, 0, 1, 4, 5, 3]):
+        after = gyro.icp_apply(arrangement, sampled, np.array(perm))
+        assert sorted(after.tolist()) == list(range(24))
+        assert gyro.assignment_cost(cost, np.array(perm)) == gyro.pruned_saliency(S[:, after])
+    # brute force of one entry straight from the definition of the 2:4 mask: keep the two largest of four
+    i, j = 2, 4
+    four = np.stack([S[:, 4 * i + m] for m in range(4) if m != sampled[i]] + [S[:, 4 * j + sampled[j]]], axis=1)
+    assert cost[i, j] == (four.sum(axis=1) - np.sort(four, axis=1)[:, 2:].sum(axis=1)).sum()
+
+
+@pytest.mark.parametrize("dtype,scored", [("f16", False), ("bf16", True)])
+def test_search_never_increases_the_objective_and_matches_the_packing_oracle(dtype, scored):
+    c = synth.small_case(32, 48, 8, 24, 4, dtype, 82)
+    Wb = c.weights()
+    rng = np.random.default_rng(83)
+    rho = rng.integers(0, 50, size=(c.M, c.K)).astype(np.float32) if scored else None
+    vec0 = orc.vector_index(Wb, dtype, c.V, c.Kv, rho)
+    iters = 4
+    samples = rng.integers(0, 4, size=(iters, c.T, c.Kv // 4))
+    vec, obj = gyro.icp_search(Wb, dtype, rho, c.V, vec0, samples)
+    for t in range(c.T):
+        assert sorted(vec[t].tolist()) == vec0[t].tolist()               # the same columns, re-arranged
+        start = gyro.pruned_saliency(gyro.kept_saliency(Wb, dtype, rho, c.V, vec0[t], t))
+        trace = [start] + obj[:, t].tolist()
+        assert all(b <= a + 1e-9 * max(1.0, abs(a)) for a, b in zip(trace, trace[1:]))
+    # the final arrangement, handed to the packing oracle as a tile-wise order, prunes exactly the final objective
+    sigma = np.stack([np.concatenate([vec[t], np.setdiff1d(np.arange(c.K), vec[t])]) for t in range(c.T)])
+    vals, nm, pvec = orc.pack(Wb, dtype, c.V, c.Kv, sigma=sigma, rho=rho)
+    assert np.array_equal(pvec, vec)
+    kept = orc.mask(nm, pvec, c.M, c.K, c.V)
+    sal = rho.astype(np.float64) if scored else np.abs(orc.decode(Wb, dtype))
+    for t in range(c.T):
+        rows = slice(t * c.V, (t + 1) * c.V)
+        pruned = sal[rows][:, vec[t]].sum() - (sal[rows] * kept[rows]).sum()
+        assert pruned == pytest.approx(obj[-1, t], rel=1e-12, abs=1e-12)
