@@ -146,6 +146,29 @@ hinm_status hinm_pack_vectors(const hinm_shape* shape, const void* W, const floa
                               void* vals_v, int32_t* vec_idx,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 4.1 (Eq. 3) / Section 4.2: tile-wise input-channel permutation search of gyro-permutation.
+ * Re-arranges the kept column vectors of every tile (vec_idx, int32 [T][Kv] as written by hinm_pack,
+ * hinm_pack_scored or hinm_pack_vectors; updated in place) so that the 2:4 step over every four
+ * consecutive ones (one partition) prunes less saliency.  Saliency of an entry: rho (float32 [M][K],
+ * as in hinm_pack_scored), or |w| when rho is NULL (then W, 16-bit [M][K], must be given).  One
+ * iteration per tile: one vector leaves every partition -- samples, uint8 [iters][T][Kv/4] in device
+ * memory, names the member (0..3, only the two low bits are read) and is drawn by the caller --;
+ * cost[i][j] (Eq. 4) = the saliency 2:4 would prune in partition i with sample j in the vacated slot
+ * (per row the two smallest of the four values, rows added in IEEE binary64 in ascending order); the
+ * samples are assigned to the partitions at minimal total cost (an exact linear-assignment solver;
+ * when several assignments reach the minimum, which one is taken is unspecified); every sample moves
+ * into the slot its partition vacated.  objective, double [iters][T] or NULL, receives that minimal
+ * total cost = the saliency the 2:4 step prunes in the tile after the iteration; it never increases.
+ * The result is a re-ordering of each row of vec_idx; hand it to hinm_pack_ordered /
+ * hinm_pack_scored as a tile order (followed by the pruned channels in any order) to pack with it.
+ * Kv above 4096 returns HINM_ERR_UNSUPPORTED.  workspace: hinm_icp_sizes bytes, 256-byte aligned.
+ * iters == 0 does nothing. */
+hinm_status hinm_icp_sizes(const hinm_shape* shape, size_t* workspace_bytes);
+hinm_status hinm_icp_search(const hinm_shape* shape, const void* W, const float* rho,
+                            int32_t* vec_idx, const uint8_t* samples, int32_t iters,
+                            double* objective,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Inverse of hinm_pack: W_out [M][K] = W_HiNM (zeros where pruned).
  * W_out is fully overwritten. */
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx,

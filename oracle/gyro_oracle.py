@@ -78,6 +78,25 @@ def icp_cost(S: np.ndarray, sampled: np.ndarray) -> np.ndarray:
     return cost
 
 
+def icp_cost_fast(S: np.ndarray, sampled: np.ndarray) -> np.ndarray:
+    """Same result as :func:`icp_cost` bit for bit (pinned in the tests), vectorised over the (i, j) pairs
+    so that full-size tiles finish in seconds; the rows are still added one after the other."""
+    V, Kv = S.shape
+    P = Kv // 4
+    sampled = np.asarray(sampled).astype(np.int64)
+    members = S.reshape(V, P, 4)
+    samp = np.take_along_axis(members, sampled[None, :, None], axis=2)[:, :, 0]            # [V, P]
+    keep = np.array([[m for m in range(4) if m != int(sampled[i])] for i in range(P)])      # [P, 3]
+    rem = np.take_along_axis(members, np.broadcast_to(keep[None], (V, P, 3)), axis=2)       # [V, P, 3]
+    cost = np.zeros((P, P), dtype=np.float64)
+    for r in range(V):
+        four = np.concatenate([np.broadcast_to(rem[r][:, None, :], (P, P, 3)),
+                               np.broadcast_to(samp[r][None, :, None], (P, P, 1))], axis=2)
+        four = np.sort(four, axis=2)
+        cost = cost + (four[:, :, 0] + four[:, :, 1])
+    return cost
+
+
 def icp_assign(cost: np.ndarray) -> np.ndarray:
     """assign[i] = the sample placed into partition i, minimising sum_i cost[i, assign[i]]."""
     rows, cols = linear_sum_assignment(cost)

@@ -117,6 +117,39 @@ hinm_status hinm_pack_vectors(const hinm_shape* shape, const void* W, const floa
                   workspace_bytes, stream);
 }
 
+static hinm_status check_icp_shape(const hinm_shape* shape) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (shape->Kv / 4 > kIcpMaxPartitions || shape->M / shape->V > 65535 || shape->V > 65535) return HINM_ERR_UNSUPPORTED;
+  return HINM_OK;
+}
+
+hinm_status hinm_icp_sizes(const hinm_shape* shape, size_t* workspace_bytes) {
+  hinm_status st = check_icp_shape(shape);
+  if (st != HINM_OK) return st;
+  if (!workspace_bytes) return HINM_ERR_NULL;
+  *workspace_bytes = icp_workspace_layout(*shape).total_bytes;
+  return HINM_OK;
+}
+
+hinm_status hinm_icp_search(const hinm_shape* shape, const void* W, const float* rho, int32_t* vec_idx,
+                            const uint8_t* samples, int32_t iters, double* objective, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  hinm_status st = check_icp_shape(shape);
+  if (st != HINM_OK) return st;
+  if ((!W && !rho) || !vec_idx || (iters > 0 && !samples)) return HINM_ERR_NULL;
+  if (iters < 0) return HINM_ERR_SHAPE;
+  if (!aligned(vec_idx, 4) || (rho && !aligned(rho, 4)) || (!rho && !aligned(W, 2)) ||
+      (objective && !aligned(objective, 8)))
+    return HINM_ERR_SHAPE;
+  const size_t need = icp_workspace_layout(*shape).total_bytes;
+  if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return HINM_ERR_WORKSPACE;
+  if (iters == 0) return HINM_OK;
+  const IcpArgs a{*shape, W, rho, vec_idx, samples, iters, objective, workspace};
+  hipError_t e = launch_icp_search(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
                         void* W_out, void* stream) {
   hinm_status st = check_shape(shape);

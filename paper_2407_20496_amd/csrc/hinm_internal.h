@@ -96,6 +96,24 @@ int spmm_vectors_variant(const VectorsArgs& a);
 hipError_t launch_spmm_vectors_mfma(const VectorsArgs& a, hipStream_t stream);
 hipError_t launch_spmm_vectors_plain(const VectorsArgs& a, hipStream_t stream);
 
+// ---- tile-wise input-channel permutation search ------------------------------------------------------
+constexpr int kIcpMaxPartitions = 1024;  // partitions (groups of four kept vectors) per tile: Kv <= 4096
+struct IcpWorkspace {  // byte offsets into the caller's workspace, each 256-byte aligned
+  size_t gathered, order, sample, min1, min2, cost, assign, total_bytes;
+};
+IcpWorkspace icp_workspace_layout(const hinm_shape& s);
+struct IcpArgs {
+  hinm_shape s;
+  const void* W;           // used when rho is NULL: saliency = |w|
+  const float* rho;        // float32 [M][K] or NULL
+  int32_t* vec_idx;        // [T][Kv], re-arranged in place
+  const uint8_t* samples;  // [iters][T][Kv/4], member 0..3 of every partition
+  int32_t iters;
+  double* objective;       // [iters][T] or NULL
+  void* workspace;
+};
+hipError_t launch_icp_search(const IcpArgs& a, hipStream_t stream);
+
 // ---- device-tuned ("prepared") layer form -------------------------------------------------------------
 hipError_t launch_prepare(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
                           const int32_t* pi_in, const int32_t* pi_out, void* prepared, hipStream_t stream);

@@ -86,6 +86,16 @@ def test_null_and_workspace_errors_are_reported_before_any_launch():
     assert vcall(flags=2 << 16) == 5     # V = 16 here: no tile kernel to pin
     assert vcall(flags=0x100 | 1 << 16) == 5
     assert vcall(flags=0x200) == 5           # HINM_KERNEL_SMFMAC has no meaning for a layer without the 2:4 mask
+    # permutation search: neither W nor rho, no samples, bad iteration count, workspace, more than 1024 partitions
+    need = C.c_size_t(0)
+    assert lib.hinm_icp_sizes(C.byref(sh), C.byref(need)) == 0 and need.value > 0
+    assert lib.hinm_icp_search(C.byref(sh), None, None, fake, fake, 1, None, fake, 1 << 30, None) == 1
+    assert lib.hinm_icp_search(C.byref(sh), fake, None, fake, None, 1, None, fake, 1 << 30, None) == 1
+    assert lib.hinm_icp_search(C.byref(sh), fake, None, fake, fake, -1, None, fake, 1 << 30, None) == 2
+    assert lib.hinm_icp_search(C.byref(sh), fake, None, fake, fake, 1, None, fake, 16, None) == 4
+    assert lib.hinm_icp_search(C.byref(sh), fake, None, fake, fake, 1, None, fake + 8, 1 << 30, None) == 4
+    wide = binding._Shape(16, 8192, 16, 4104, 0)
+    assert lib.hinm_icp_sizes(C.byref(wide), C.byref(need)) == 5
     # spmm: null X, bad N, bad ld, misaligned X, unknown flag, two kernels forced
     args = dict(N=64, vals=fake, nm=fake, vec=fake, X=fake, ldx=64, Y=fake, ldy=64, flags=0)
 

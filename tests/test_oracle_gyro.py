@@ -86,3 +86,10 @@ def test_search_never_increases_the_objective_and_matches_the_packing_oracle(dty
         rows = slice(t * c.V, (t + 1) * c.V)
         pruned = sal[rows][:, vec[t]].sum() - (sal[rows] * kept[rows]).sum()
         assert pruned == pytest.approx(obj[-1, t], rel=1e-12, abs=1e-12)
+
+
+def test_fast_cost_is_the_plain_cost_bit_for_bit():
+    rng = np.random.default_rng(84)
+    S = (rng.standard_normal((7, 40)) ** 2).astype(np.float32).astype(np.float64)   # sums that do round
+    sampled = rng.integers(0, 4, size=10)
+    assert np.array_equal(gyro.icp_cost_fast(S, sampled), gyro.icp_cost(S, sampled))
