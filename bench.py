@@ -42,6 +42,8 @@ PACK_WORKLOADS = ("pack-c5", "pack-c5-ordered", "pack-c5-scored", "pack-c5-vecto
 
 
 SWEEP_WORKLOADS = ("sweep-bert", "sweep-resnet")
+ICP_WORKLOADS = ("icp-c2", "icp-c4")
+FP64_ADD_PEAK_TOPS = 39.3         # 256 compute units x 64 lanes x 2.4 GHz = half the fp64 FMA flop figure
 
 
 def workloads():
@@ -76,6 +78,8 @@ def main():
                     help="number of rotated buffer sets (default: enough to exceed the Infinity Cache)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--kernel-us", type=float, default=None,
+                    help="icp workloads: average duration of icp_cost_kernel from a rocprofv3 summary, to price it")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step from the host instead of replaying one captured HIP graph of K steps")
     args = ap.parse_args()
@@ -96,11 +100,14 @@ def main():
         return bench_pack(args, torch, hinm, dev)
     if args.workload in SWEEP_WORKLOADS:
         return bench_sweep(args, torch, hinm, dev)
+    if args.workload in ICP_WORKLOADS:
+        return bench_icp(args, torch, hinm, dev)
     wl = workloads()
     if args.workload.startswith("vectors-") and args.workload[8:] in wl:
         return bench_vectors(args, torch, hinm, dev, wl[args.workload[8:]])
     if args.workload not in wl:
-        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS + SWEEP_WORKLOADS) + " " + " ".join(wl)
+        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS + SWEEP_WORKLOADS + ICP_WORKLOADS) + " "
+              + " ".join(wl)
               + " vectors-<any of the latter>", file=sys.stderr)
         sys.exit(2)
     c = wl[args.workload]
@@ -499,6 +506,64 @@ def bench_vectors(args, torch, hinm, dev, c):
                       "launch": "one HIP graph of K steps"},
            "stored_value_tflops": round(flops / (kernel_ms * 1e-3) / 1e12, 3), "roofline": roofline,
            "cpu_baseline": None}
+    print(json.dumps(out))
+
+
+def bench_icp(args, torch, hinm, dev):
+    """Tile-wise input-channel permutation search (hinm_icp_search) on a packed layer: K iterations in one call,
+    samples drawn on the host from a seeded generator.  `value` = iterations per second over all tiles; the
+    roofline object prices the cost-matrix kernel (two binary64 additions per partition x sample x row) against
+    the binary64 add rate of the vector units."""
+    c = synth.c2() if args.workload == "icp-c2" else synth.c4()
+    P = c.Kv // 4
+    W = torch.from_numpy(c.weights().view(np.int16)).to(dev)
+    vb, nb, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+    vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
+    nm = torch.empty(nb, dtype=torch.uint8, device=dev)
+    vec0 = torch.empty(cb // 4, dtype=torch.int32, device=dev)
+    ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
+    hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec0, ws, wb)
+    del ws
+    steps = args.steps or 20
+    warmup = args.warmup or 2
+    rng = np.random.default_rng(20496)
+    samples = torch.from_numpy(rng.integers(0, 4, size=(steps, c.T, P), dtype=np.uint8)).to(dev)
+    wsb = hinm.hinm_icp_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+    work = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    obj = torch.zeros((steps, c.T), dtype=torch.float64, device=dev)
+    vec = vec0.clone()
+    hinm.hinm_icp_search(c.M, c.K, c.V, c.Kv, c.dtype, W, None, vec, samples, warmup, obj, work, wsb)
+    torch.cuda.synchronize()
+    vec.copy_(vec0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    hinm.hinm_icp_search(c.M, c.K, c.V, c.Kv, c.dtype, W, None, vec, samples, steps, obj, work, wsb)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms = e0.elapsed_time(e1) / steps
+    o = obj.cpu().numpy()
+    # per-kernel share from a short second run under events is not available here; the cost kernel's own time
+    # is in the rocprofv3 summary.  Its work per iteration:
+    adds = 2.0 * c.T * P * P * c.V
+    out = {"metric": "hinm_icp_iterations_per_s", "value": round(1e3 / ms, 2), "unit": "iterations/s", "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": round(wall_ms, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": "tile-wise input-channel permutation search on " + c.name, "tiles": c.T,
+                      "partitions_per_tile": P, "rows_per_tile": c.V,
+                      "pruned_saliency_first_iteration": float(o[0].sum()),
+                      "pruned_saliency_last_iteration": float(o[-1].sum())},
+           "gpu_ms_per_iteration": round(ms, 4),
+           "roofline": {"bound": "alu", "kernel": "icp_cost_kernel", "achieved": None, "peak": FP64_ADD_PEAK_TOPS,
+                        "unit": "Tadd/s (binary64)", "frac": None, "traffic": None,
+                        "adds_per_launch": adds,
+                        "note": "achieved = adds_per_launch / the kernel's average duration in the rocprofv3 summary"},
+           "cpu_baseline": None}
+    if args.kernel_us:
+        ach = adds / (args.kernel_us * 1e-6) / 1e12
+        out["roofline"].update({"achieved": round(ach, 3), "frac": round(ach / FP64_ADD_PEAK_TOPS, 4),
+                                "kernel_us_avg": args.kernel_us})
     print(json.dumps(out))
 
 

@@ -20,6 +20,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxP = kIcpMaxPartitions;
+constexpr int kSmallP = 128;  // up to here a tile's cost matrix fits in LDS
 constexpr int kCostRowsPerThread = 8;
 constexpr double kInf = 1e300;
 
@@ -109,18 +110,26 @@ __global__ __launch_bounds__(kThreads) void icp_cost_kernel(const float* __restr
 // workgroup per tile.  Index 0 is the virtual start column; rows and columns are 1-based inside.
 // Every loop is bounded by the problem size, so the kernel ends for any input; if the costs are not
 // finite no augmenting path is found and the tile keeps its arrangement (identity assignment).
-__global__ __launch_bounds__(kThreads) void icp_assign_kernel(const double* __restrict__ cost,
-                                                              int32_t* __restrict__ assign, int n) {
-  __shared__ double u[kMaxP + 1], v[kMaxP + 1], minv[kMaxP + 1];
-  __shared__ int p[kMaxP + 1], way[kMaxP + 1];
-  __shared__ uint8_t used[kMaxP + 1];
-  __shared__ double red_val[kThreads / 64];
-  __shared__ int red_idx[kThreads / 64];
+// Each of the up to n^2 inner steps reads one row of the cost matrix and is one dependent chain of
+// memory latency, reduction and barriers: for n <= MAXN = 128 the matrix is held in LDS (IN_LDS) and
+// the workgroup has two waves, which makes a step about three times shorter.
+template <int MAXN, int THREADS, bool IN_LDS>
+__global__ __launch_bounds__(THREADS) void icp_assign_kernel(const double* __restrict__ cost,
+                                                             int32_t* __restrict__ assign, int n) {
+  __shared__ double u[MAXN + 1], v[MAXN + 1], minv[MAXN + 1];
+  __shared__ int p[MAXN + 1], way[MAXN + 1];
+  __shared__ uint8_t used[MAXN + 1];
+  __shared__ double red_val[THREADS / 64];
+  __shared__ int red_idx[THREADS / 64];
+  extern __shared__ __attribute__((aligned(16))) double cost_lds[];  // n * n doubles when IN_LDS
   const int t = blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const double* a = cost + (size_t)t * n * n;
-  for (int j = tid; j <= n; j += kThreads) {
+  if constexpr (IN_LDS) {
+    for (int e = tid; e < n * n; e += THREADS) cost_lds[e] = a[e];
+  }
+  for (int j = tid; j <= n; j += THREADS) {
     u[j] = 0.0;
     v[j] = 0.0;
     p[j] = 0;
@@ -130,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void icp_assign_kernel(const double* __re
   bool failed = false;
   for (int i = 1; i <= n && !failed; ++i) {
     if (tid == 0) p[0] = i;
-    for (int j = tid; j <= n; j += kThreads) {
+    for (int j = tid; j <= n; j += THREADS) {
       minv[j] = kInf;
       used[j] = 0;
     }
@@ -141,10 +150,10 @@ __global__ __launch_bounds__(kThreads) void icp_assign_kernel(const double* __re
       __syncthreads();
       const int i0 = p[j0];
       const double ui0 = u[i0];
-      const double* arow = a + (size_t)(i0 - 1) * n;
+      const double* arow = (IN_LDS ? cost_lds : a) + (size_t)(i0 - 1) * n;
       double best = kInf;
       int best_j = n + 1;
-      for (int j = 1 + tid; j <= n; j += kThreads) {
+      for (int j = 1 + tid; j <= n; j += THREADS) {
         if (used[j]) continue;
         const double cur = arow[j - 1] - ui0 - v[j];
         double m = minv[j];
@@ -175,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void icp_assign_kernel(const double* __re
       double delta = red_val[0];
       int j1 = red_idx[0];
 #pragma unroll
-      for (int w = 1; w < kThreads / 64; ++w) {
+      for (int w = 1; w < THREADS / 64; ++w) {
         const double ob = red_val[w];
         const int oj = red_idx[w];
         if (ob < delta || (ob == delta && oj < j1)) {
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void icp_assign_kernel(const double* __re
         failed = true;
         break;
       }
-      for (int j = tid; j <= n; j += kThreads) {
+      for (int j = tid; j <= n; j += THREADS) {
         if (used[j]) {
           u[p[j]] += delta;  // the rows matched to used columns are distinct
           v[j] -= delta;
@@ -212,9 +221,9 @@ __global__ __launch_bounds__(kThreads) void icp_assign_kernel(const double* __re
   }
   int32_t* out = assign + (size_t)t * n;
   if (failed) {
-    for (int i = tid; i < n; i += kThreads) out[i] = i;
+    for (int i = tid; i < n; i += THREADS) out[i] = i;
   } else {
-    for (int j = 1 + tid; j <= n; j += kThreads) {
+    for (int j = 1 + tid; j <= n; j += THREADS) {
       const int row = p[j];
       if (row >= 1) out[row - 1] = j - 1;
     }
@@ -304,12 +313,21 @@ hipError_t launch_icp_search(const IcpArgs& a, hipStream_t stream) {
     icp_gather_kernel<HINM_BF16><<<rows_grid, kThreads, 0, stream>>>(Wb, a.rho, a.vec_idx, G, order, s.K, s.V, s.Kv);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (P <= kSmallP) {  // the cost matrix of a tile in LDS: up to 128 KB beside the solver's own arrays
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(icp_assign_kernel<kSmallP, 128, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kSmallP * kSmallP * (int)sizeof(double));
+    if (e != hipSuccess) return e;
+  }
   const dim3 cost_grid((P + kThreads - 1) / kThreads, (P + kCostRowsPerThread - 1) / kCostRowsPerThread, T);
   for (int it = 0; it < a.iters; ++it) {
     const uint8_t* smp = a.samples + (size_t)it * T * P;
     icp_split_kernel<<<rows_grid, kThreads, 0, stream>>>(G, order, smp, S, M1, M2, s.V, s.Kv);
     icp_cost_kernel<<<cost_grid, kThreads, 0, stream>>>(S, M1, M2, cost, s.V, P);
-    icp_assign_kernel<<<T, kThreads, 0, stream>>>(cost, assign, P);
+    if (P <= kSmallP) {
+      icp_assign_kernel<kSmallP, 128, true><<<T, 128, (size_t)P * P * sizeof(double), stream>>>(cost, assign, P);
+    } else {
+      icp_assign_kernel<kMaxP, kThreads, false><<<T, kThreads, 0, stream>>>(cost, assign, P);
+    }
     icp_apply_kernel<<<T, kThreads, 0, stream>>>(cost, assign, smp, order,
                                                  a.objective ? a.objective + (size_t)it * T : nullptr, s.Kv);
     e = hipGetLastError();
