@@ -1,4 +1,5 @@
-"""CPU oracle for the tile-wise input-channel permutation search of gyro-permutation.
+"""CPU oracle for the two permutation searches of gyro-permutation: tile-wise input channels
+(icp_*) and output channels (ocp_*).
 
 TEST INFRASTRUCTURE ONLY.  Slow, plain definition of what the HIP library's search computes; it
 shares no code with the HIP path and must never be imported by it.
@@ -13,20 +14,34 @@ What it follows (arXiv 2407.20496):
     and an assignment of samples to partitions that minimises the total cost (the paper names the
     Hungarian algorithm; any exact solver of the linear assignment problem reaches the same minimum).
 
+  * Section 4.1, Eq. 2 and Section 4.2 for the output channels: the partitions are the tiles of V
+    output channels; the same number of channels is sampled from every tile, the sampled channels are
+    grouped into as many clusters as there are tiles (the paper uses balanced K-means; here the grouping
+    is an input, by default every tile's own samples form a cluster), cost[i][j] (Eq. 4) is the
+    saliency column-vector pruning would remove from tile i's remaining channels plus cluster j, and
+    the clusters are assigned to the tiles at minimal total cost.
+
 Readings where the paper is silent (repeated in the design notes): which member of a partition is
 sampled is an input (the caller draws it); a sample moves into the slot its destination partition
 vacated; the cost is the plain sum of the pruned saliencies (not total minus retained), per row the
 two smallest of the four values added exactly, rows accumulated in binary64 in ascending order;
 saliency = caller-given rho (float32) or |w|; several assignments may reach the minimum, any of
-them is a correct result, and the number of iterations is the caller's.
+them is a correct result, and the number of iterations is the caller's.  Output channels: the column
+scores of a candidate tile are (sum over the remaining channels in position order) + (sum over the
+cluster's channels in cluster order), each in binary64; the cost is the sum of the K - Kv smallest
+scores (which of several equal scores is pruned does not change it), here added with exact rounding;
+the channels of a cluster fill the slots the tile vacated in position order.
 
 Pins: tests/test_oracle_gyro.py (brute force over all assignments, the hand-derived example in
 tests/golden/hand_example_icp.txt, cost of the identity assignment = current pruned saliency,
 total cost of an assignment = pruned saliency after the move, the objective never increases, and
-the final arrangement fed to the packing oracle prunes exactly the final objective).
+the final arrangement fed to the packing oracle prunes exactly the final objective; for the output
+channels a second hand-derived example, brute force over assignments, and the vector scores of the
+packing oracle on the re-ordered matrix).
 """
 from __future__ import annotations
 
+import math
 from typing import Optional, Tuple
 
 import numpy as np
@@ -138,3 +153,87 @@ def icp_search(W_bits: np.ndarray, dtype: str, rho: Optional[np.ndarray], V: int
             objective[it, t] = assignment_cost(cost, assign)
             vec[t] = icp_apply(vec[t], samples[it, t], assign)
     return vec, objective
+
+
+# --------------------------------------------------------------------------
+# Section 4.1 Eq. 2 / Section 4.2: output-channel permutation
+# --------------------------------------------------------------------------
+
+
+def saliency_matrix(W_bits: np.ndarray, dtype: str, rho: Optional[np.ndarray]) -> np.ndarray:
+    """float64 [M, K]: the caller's rho, or |w|."""
+    if rho is not None:
+        return np.asarray(rho).astype(np.float64)
+    return np.abs(orc.decode(W_bits, dtype))
+
+
+def vector_pruned_saliency(S_rows: np.ndarray, Kv: int) -> float:
+    """S_rows: float64 [V, K], the channels of one tile in position order.  What column-vector pruning
+    removes: the sum of the K - Kv smallest column sums (rows added in order, binary64)."""
+    V, K = S_rows.shape
+    col = np.zeros(K, dtype=np.float64)
+    for r in range(V):
+        col = col + S_rows[r]
+    return math.fsum(np.sort(col)[:K - Kv].tolist())
+
+
+def ocp_cost(S: np.ndarray, rows: np.ndarray, sampled: np.ndarray, clusters: Optional[np.ndarray], Kv: int) -> np.ndarray:
+    """Eq. 4 for the output channels.  S: float64 [M, K] saliency; rows: int [T, V], rows[t, p] = the
+    channel at position p of tile t; sampled: int [T, n] distinct positions taken out of every tile;
+    clusters: int [T, n], a grouping of the T * n sampled channels (item q = sample q % n of tile
+    q // n) into T clusters, None = every tile's own samples.  cost[i, j] = saliency that vector pruning
+    removes from tile i's remaining channels plus cluster j: float64 [T, T]."""
+    T, V = rows.shape
+    n = sampled.shape[1]
+    K = S.shape[1]
+    if clusters is None:
+        clusters = np.arange(T * n).reshape(T, n)
+    pool = [int(rows[q // n, sampled[q // n, q % n]]) for q in range(T * n)]
+    base = np.zeros((T, K), dtype=np.float64)
+    clus = np.zeros((T, K), dtype=np.float64)
+    for t in range(T):
+        out = set(int(x) for x in sampled[t])
+        assert len(out) == n
+        for pos in range(V):
+            if pos not in out:
+                base[t] = base[t] + S[rows[t, pos]]
+        for e in range(n):
+            clus[t] = clus[t] + S[pool[int(clusters[t, e])]]
+    cost = np.zeros((T, T), dtype=np.float64)
+    for i in range(T):
+        for j in range(T):
+            col = base[i] + clus[j]
+            cost[i, j] = math.fsum(np.sort(col)[:K - Kv].tolist())
+    return cost
+
+
+def ocp_apply(rows: np.ndarray, sampled: np.ndarray, clusters: Optional[np.ndarray], assign: np.ndarray) -> np.ndarray:
+    """The channels of cluster assign[i] fill the positions tile i vacated, in order."""
+    T, V = rows.shape
+    n = sampled.shape[1]
+    if clusters is None:
+        clusters = np.arange(T * n).reshape(T, n)
+    pool = [int(rows[q // n, sampled[q // n, q % n]]) for q in range(T * n)]
+    out = np.array(rows, copy=True)
+    for i in range(T):
+        for e in range(n):
+            out[i, sampled[i, e]] = pool[int(clusters[int(assign[i]), e])]
+    return out
+
+
+def ocp_search(W_bits: np.ndarray, dtype: str, rho: Optional[np.ndarray], V: int, Kv: int, row_order: np.ndarray,
+               samples: np.ndarray, clusters: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """row_order: int [M], row_order[t * V + p] = the channel at position p of tile t.  samples:
+    [iters, T, n]; clusters: [iters, T, n] or None.  Returns (row order after all iterations [M],
+    objective [iters] = saliency removed by vector pruning over all tiles after each iteration)."""
+    S = saliency_matrix(W_bits, dtype, rho)
+    rows = np.array(row_order, copy=True).reshape(-1, V)
+    iters = samples.shape[0]
+    objective = np.zeros(iters, dtype=np.float64)
+    for it in range(iters):
+        cl = None if clusters is None else clusters[it]
+        cost = ocp_cost(S, rows, samples[it], cl, Kv)
+        assign = icp_assign(cost)
+        objective[it] = assignment_cost(cost, assign)
+        rows = ocp_apply(rows, samples[it], cl, assign)
+    return rows.reshape(-1), objective

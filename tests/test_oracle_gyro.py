@@ -93,3 +93,67 @@ def test_fast_cost_is_the_plain_cost_bit_for_bit():
     S = (rng.standard_normal((7, 40)) ** 2).astype(np.float32).astype(np.float64)   # sums that do round
     sampled = rng.integers(0, 4, size=10)
     assert np.array_equal(gyro.icp_cost_fast(S, sampled), gyro.icp_cost(S, sampled))
+
+
+# ---- output channels ------------------------------------------------------------------------------------
+
+def test_hand_example_output_channels():
+    ex = load_golden("hand_example_ocp.txt")
+    S = ex["rho"].astype(np.float64)
+    rows = ex["row_order"].reshape(2, 2)
+    cost = gyro.ocp_cost(S, rows, ex["samples"], None, 2)
+    assert cost.tolist() == ex["cost"].astype(np.float64).tolist()
+    assign = gyro.icp_assign(cost)
+    assert assign.tolist() == ex["assign"].reshape(-1).tolist()
+    after = gyro.ocp_apply(rows, ex["samples"], None, assign)
+    assert after.reshape(-1).tolist() == ex["row_order_after"].reshape(-1).tolist()
+    Wb = synth.to_bits(ex["rho"].astype(np.float32), "bf16")
+    order, obj = gyro.ocp_search(Wb, "bf16", None, 2, 2, ex["row_order"].reshape(-1), ex["samples"].reshape(1, 2, 1))
+    assert order.tolist() == ex["row_order_after"].reshape(-1).tolist() and obj.tolist() == [16.0]
+
+
+def _ocp_case(seed, T=4, V=6, K=10, n=2):
+    rng = np.random.default_rng(seed)
+    S = rng.integers(0, 9, size=(T * V, K)).astype(np.float64)
+    rows = rng.permutation(T * V).reshape(T, V)
+    sampled = np.stack([rng.permutation(V)[:n] for _ in range(T)])
+    clusters = rng.permutation(T * n).reshape(T, n)
+    return S, rows, sampled, clusters
+
+
+def test_output_channel_cost_against_the_packing_oracle_and_brute_force():
+    import itertools
+    T, V, K, n, Kv = 4, 6, 10, 2, 8      # Kv % 8 == 0 so that the packing oracle accepts the shape
+    S, rows, sampled, clusters = _ocp_case(85, T, V, K, n)
+    for cl in (None, clusters):
+        cost = gyro.ocp_cost(S, rows, sampled, cl, Kv)
+        assign = gyro.icp_assign(cost)
+        best = min(sum(cost[i, p[i]] for i in range(T)) for p in itertools.permutations(range(T)))
+        assert gyro.assignment_cost(cost, assign) == best
+        for perm in (np.arange(T), assign, np.array([3, 2, 1, 0])):
+            after = gyro.ocp_apply(rows, sampled, cl, perm)
+            assert sorted(after.reshape(-1).tolist()) == list(range(T * V))        # still a permutation of the channels
+            # the vector scores of the packing oracle on the re-ordered saliency: what is not kept is the cost
+            R = S[after.reshape(-1)].astype(np.float32)
+            scores = orc.vector_scores_rho(R, V)
+            kept = orc.vector_index(np.zeros((T * V, K), dtype=np.uint16), "f16", V, Kv, rho=R)
+            pruned = sum(scores[t].sum() - scores[t][kept[t]].sum() for t in range(T))
+            assert pruned == gyro.assignment_cost(cost, perm)
+    # with every tile's own samples as its cluster nothing moves under the identity assignment
+    assert np.array_equal(gyro.ocp_apply(rows, sampled, None, np.arange(T)), rows)
+
+
+def test_output_channel_search_never_increases_the_objective():
+    c = synth.small_case(48, 40, 8, 16, 4, "f16", 86)
+    Wb = c.weights()
+    rng = np.random.default_rng(87)
+    iters, n = 4, 3
+    samples = np.stack([np.stack([rng.permutation(c.V)[:n] for _ in range(c.T)]) for _ in range(iters)])
+    order, obj = gyro.ocp_search(Wb, c.dtype, None, c.V, c.Kv, np.arange(c.M), samples)
+    assert sorted(order.tolist()) == list(range(c.M))
+    S = gyro.saliency_matrix(Wb, c.dtype, None)
+    start = sum(gyro.vector_pruned_saliency(S[t * c.V:(t + 1) * c.V], c.Kv) for t in range(c.T))
+    seq = [start] + obj.tolist()
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(seq, seq[1:]))
+    end = sum(gyro.vector_pruned_saliency(S[order[t * c.V:(t + 1) * c.V]], c.Kv) for t in range(c.T))
+    assert end == pytest.approx(obj[-1], rel=1e-12)
