@@ -169,6 +169,29 @@ hinm_status hinm_icp_search(const hinm_shape* shape, const void* W, const float*
                             double* objective,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 4.1 (Eq. 2) / Section 4.2: output-channel permutation search of gyro-permutation.
+ * Re-distributes the output channels over the tiles so that column-vector pruning (keep the Kv
+ * columns of largest summed saliency per tile) removes less saliency.  row_order, int32 [M] in device
+ * memory, updated in place: row_order[t V + p] = the channel (row of W / rho) at position p of tile
+ * t; start from 0..M-1.  Saliency as in hinm_icp_search (rho, or |w| when rho is NULL).  One
+ * iteration: n_samples channels leave every tile -- samples, int32 [iters][T][n_samples], distinct
+ * positions 0..V-1, drawn by the caller --; the T n_samples sampled channels (item q = sample
+ * q % n_samples of tile q / n_samples) are grouped into T clusters -- clusters, int32
+ * [iters][T][n_samples], a permutation of the items, computed by the caller (the paper uses balanced
+ * K-means), or NULL = every tile's own samples --; cost[i][j] (Eq. 4) = the saliency vector pruning
+ * would remove from tile i's remaining channels plus cluster j (sum of the K - Kv smallest column
+ * scores, binary64); clusters are assigned to tiles at minimal total cost; the channels of the
+ * assigned cluster fill the vacated positions in order.  objective, double [iters] or NULL: that
+ * minimal total cost.  Apply the result by packing the rows of W in this order (and composing pi_out
+ * with it).  Entries of samples, clusters and row_order are not checked; out-of-range values are
+ * clamped into range, which gives a meaningless order.  T above 1024, K above 16384 or V above 4096
+ * return HINM_ERR_UNSUPPORTED.  workspace: hinm_ocp_sizes bytes, 256-byte aligned. */
+hinm_status hinm_ocp_sizes(const hinm_shape* shape, int32_t n_samples, size_t* workspace_bytes);
+hinm_status hinm_ocp_search(const hinm_shape* shape, const void* W, const float* rho,
+                            int32_t* row_order, const int32_t* samples, const int32_t* clusters,
+                            int32_t n_samples, int32_t iters, double* objective,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Inverse of hinm_pack: W_out [M][K] = W_HiNM (zeros where pruned).
  * W_out is fully overwritten. */
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx,

@@ -150,6 +150,40 @@ hinm_status hinm_icp_search(const hinm_shape* shape, const void* W, const float*
   return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 
+static hinm_status check_ocp_shape(const hinm_shape* shape, int32_t n_samples) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (n_samples < 1 || n_samples > shape->V) return HINM_ERR_SHAPE;
+  if (shape->M / shape->V > kIcpMaxPartitions || shape->K > kOcpMaxK || shape->V > kOcpMaxV) return HINM_ERR_UNSUPPORTED;
+  return HINM_OK;
+}
+
+hinm_status hinm_ocp_sizes(const hinm_shape* shape, int32_t n_samples, size_t* workspace_bytes) {
+  hinm_status st = check_ocp_shape(shape, n_samples);
+  if (st != HINM_OK) return st;
+  if (!workspace_bytes) return HINM_ERR_NULL;
+  *workspace_bytes = ocp_workspace_layout(*shape, n_samples).total_bytes;
+  return HINM_OK;
+}
+
+hinm_status hinm_ocp_search(const hinm_shape* shape, const void* W, const float* rho, int32_t* row_order,
+                            const int32_t* samples, const int32_t* clusters, int32_t n_samples, int32_t iters,
+                            double* objective, void* workspace, size_t workspace_bytes, void* stream) {
+  hinm_status st = check_ocp_shape(shape, n_samples);
+  if (st != HINM_OK) return st;
+  if ((!W && !rho) || !row_order || (iters > 0 && !samples)) return HINM_ERR_NULL;
+  if (iters < 0) return HINM_ERR_SHAPE;
+  if (!aligned(row_order, 4) || !aligned(samples, 4) || !aligned(clusters, 4) || (rho && !aligned(rho, 4)) ||
+      (!rho && !aligned(W, 2)) || (objective && !aligned(objective, 8)))
+    return HINM_ERR_SHAPE;
+  const size_t need = ocp_workspace_layout(*shape, n_samples).total_bytes;
+  if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return HINM_ERR_WORKSPACE;
+  if (iters == 0) return HINM_OK;
+  const OcpArgs a{*shape, W, rho, row_order, samples, clusters, n_samples, iters, objective, workspace};
+  hipError_t e = launch_ocp_search(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
                         void* W_out, void* stream) {
   hinm_status st = check_shape(shape);

@@ -113,6 +113,30 @@ struct IcpArgs {
   void* workspace;
 };
 hipError_t launch_icp_search(const IcpArgs& a, hipStream_t stream);
+// `problems` independent n x n linear assignment problems (cost row-major, binary64), n <= kIcpMaxPartitions:
+// assign[q][i] = the column given to row i at minimal total cost
+hipError_t launch_assignment(const double* cost, int32_t* assign, int problems, int n, hipStream_t stream);
+
+// ---- output-channel permutation search ---------------------------------------------------------------
+constexpr int kOcpMaxK = 16384;   // columns one workgroup of the cost kernel holds in registers
+constexpr int kOcpMaxV = 4096;    // positions of a tile (flags in LDS)
+struct OcpWorkspace {
+  size_t base, cluster, cost, assign, moved, total_bytes;
+};
+OcpWorkspace ocp_workspace_layout(const hinm_shape& s, int n_samples);
+struct OcpArgs {
+  hinm_shape s;
+  const void* W;            // used when rho is NULL: saliency = |w|
+  const float* rho;         // float32 [M][K] or NULL
+  int32_t* row_order;       // [M], row_order[t V + p] = the channel at position p of tile t; updated in place
+  const int32_t* samples;   // [iters][T][n] positions 0..V-1
+  const int32_t* clusters;  // [iters][T][n] items 0..T n - 1 grouped into clusters, or NULL
+  int32_t n_samples;
+  int32_t iters;
+  double* objective;        // [iters] or NULL
+  void* workspace;
+};
+hipError_t launch_ocp_search(const OcpArgs& a, hipStream_t stream);
 
 // ---- device-tuned ("prepared") layer form -------------------------------------------------------------
 hipError_t launch_prepare(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,

@@ -278,6 +278,19 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }  // namespace
 
+hipError_t launch_assignment(const double* cost, int32_t* assign, int problems, int n, hipStream_t stream) {
+  if (n <= kSmallP) {  // the cost matrix in LDS: up to 128 KB beside the solver's own arrays
+    auto kernel = icp_assign_kernel<kSmallP, 128, true>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kSmallP * kSmallP * (int)sizeof(double));
+    if (e != hipSuccess) return e;
+    kernel<<<problems, 128, (size_t)n * n * sizeof(double), stream>>>(cost, assign, n);
+  } else {
+    icp_assign_kernel<kMaxP, kThreads, false><<<problems, kThreads, 0, stream>>>(cost, assign, n);
+  }
+  return hipGetLastError();
+}
+
 IcpWorkspace icp_workspace_layout(const hinm_shape& s) {
   const size_t T = s.M / s.V, P = s.Kv / 4;
   IcpWorkspace w;
@@ -313,21 +326,13 @@ hipError_t launch_icp_search(const IcpArgs& a, hipStream_t stream) {
     icp_gather_kernel<HINM_BF16><<<rows_grid, kThreads, 0, stream>>>(Wb, a.rho, a.vec_idx, G, order, s.K, s.V, s.Kv);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (P <= kSmallP) {  // the cost matrix of a tile in LDS: up to 128 KB beside the solver's own arrays
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(icp_assign_kernel<kSmallP, 128, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kSmallP * kSmallP * (int)sizeof(double));
-    if (e != hipSuccess) return e;
-  }
   const dim3 cost_grid((P + kThreads - 1) / kThreads, (P + kCostRowsPerThread - 1) / kCostRowsPerThread, T);
   for (int it = 0; it < a.iters; ++it) {
     const uint8_t* smp = a.samples + (size_t)it * T * P;
     icp_split_kernel<<<rows_grid, kThreads, 0, stream>>>(G, order, smp, S, M1, M2, s.V, s.Kv);
     icp_cost_kernel<<<cost_grid, kThreads, 0, stream>>>(S, M1, M2, cost, s.V, P);
-    if (P <= kSmallP) {
-      icp_assign_kernel<kSmallP, 128, true><<<T, 128, (size_t)P * P * sizeof(double), stream>>>(cost, assign, P);
-    } else {
-      icp_assign_kernel<kMaxP, kThreads, false><<<T, kThreads, 0, stream>>>(cost, assign, P);
-    }
+    e = launch_assignment(cost, assign, T, P, stream);
+    if (e != hipSuccess) return e;
     icp_apply_kernel<<<T, kThreads, 0, stream>>>(cost, assign, smp, order,
                                                  a.objective ? a.objective + (size_t)it * T : nullptr, s.Kv);
     e = hipGetLastError();

@@ -96,6 +96,16 @@ def test_null_and_workspace_errors_are_reported_before_any_launch():
     assert lib.hinm_icp_search(C.byref(sh), fake, None, fake, fake, 1, None, fake + 8, 1 << 30, None) == 4
     wide = binding._Shape(16, 8192, 16, 4104, 0)
     assert lib.hinm_icp_sizes(C.byref(wide), C.byref(need)) == 5
+    # output-channel search: sample count, nulls, workspace, limits
+    assert lib.hinm_ocp_sizes(C.byref(sh), 0, C.byref(need)) == 2
+    assert lib.hinm_ocp_sizes(C.byref(sh), 17, C.byref(need)) == 2          # more samples than channels in a tile
+    assert lib.hinm_ocp_sizes(C.byref(sh), 4, C.byref(need)) == 0 and need.value > 0
+    assert lib.hinm_ocp_search(C.byref(sh), None, None, fake, fake, None, 4, 1, None, fake, 1 << 30, None) == 1
+    assert lib.hinm_ocp_search(C.byref(sh), fake, None, None, fake, None, 4, 1, None, fake, 1 << 30, None) == 1
+    assert lib.hinm_ocp_search(C.byref(sh), fake, None, fake, fake, None, 4, 1, None, fake, 16, None) == 4
+    assert lib.hinm_ocp_search(C.byref(sh), fake, None, fake, fake + 2, None, 4, 1, None, fake, 1 << 30, None) == 2
+    many = binding._Shape(32768, 64, 16, 32, 0)                                # 2048 tiles
+    assert lib.hinm_ocp_sizes(C.byref(many), 1, C.byref(need)) == 5
     # spmm: null X, bad N, bad ld, misaligned X, unknown flag, two kernels forced
     args = dict(N=64, vals=fake, nm=fake, vec=fake, X=fake, ldx=64, Y=fake, ldy=64, flags=0)
 
