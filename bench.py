@@ -43,6 +43,7 @@ PACK_WORKLOADS = ("pack-c5", "pack-c5-ordered", "pack-c5-scored", "pack-c5-vecto
 
 SWEEP_WORKLOADS = ("sweep-bert", "sweep-resnet")
 ICP_WORKLOADS = ("icp-c2", "icp-c4")
+OCP_WORKLOADS = ("ocp-c2", "ocp-c5")
 FP64_ADD_PEAK_TOPS = 39.3         # 256 compute units x 64 lanes x 2.4 GHz = half the fp64 FMA flop figure
 
 
@@ -79,7 +80,7 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--kernel-us", type=float, default=None,
-                    help="icp workloads: average duration of icp_cost_kernel from a rocprofv3 summary, to price it")
+                    help="icp / ocp workloads: average duration of the cost kernel from a rocprofv3 summary, to price it")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step from the host instead of replaying one captured HIP graph of K steps")
     args = ap.parse_args()
@@ -102,11 +103,13 @@ def main():
         return bench_sweep(args, torch, hinm, dev)
     if args.workload in ICP_WORKLOADS:
         return bench_icp(args, torch, hinm, dev)
+    if args.workload in OCP_WORKLOADS:
+        return bench_ocp(args, torch, hinm, dev)
     wl = workloads()
     if args.workload.startswith("vectors-") and args.workload[8:] in wl:
         return bench_vectors(args, torch, hinm, dev, wl[args.workload[8:]])
     if args.workload not in wl:
-        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS + SWEEP_WORKLOADS + ICP_WORKLOADS) + " "
+        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS + SWEEP_WORKLOADS + ICP_WORKLOADS + OCP_WORKLOADS) + " "
               + " ".join(wl)
               + " vectors-<any of the latter>", file=sys.stderr)
         sys.exit(2)
@@ -562,6 +565,54 @@ def bench_icp(args, torch, hinm, dev):
            "cpu_baseline": None}
     if args.kernel_us:
         ach = adds / (args.kernel_us * 1e-6) / 1e12
+        out["roofline"].update({"achieved": round(ach, 3), "frac": round(ach / FP64_ADD_PEAK_TOPS, 4),
+                                "kernel_us_avg": args.kernel_us})
+    print(json.dumps(out))
+
+
+def bench_ocp(args, torch, hinm, dev):
+    """Output-channel permutation search (hinm_ocp_search) on a dense layer: K iterations in one call, samples
+    drawn on the host from a seeded generator, every tile's own samples as its cluster.  `value` = iterations
+    per second; the roofline object prices the cost kernel (64 counting passes of 64-bit compares over the K
+    column scores of every tile x cluster pair) against the 64-bit rate of the vector units."""
+    c = synth.c2() if args.workload == "ocp-c2" else synth.c5()
+    n = max(1, c.V // 8)
+    W = torch.from_numpy(c.weights().view(np.int16)).to(dev)
+    steps = args.steps or 10
+    warmup = args.warmup or 2
+    rng = np.random.default_rng(20496)
+    samples = torch.from_numpy(np.stack([np.stack([rng.permutation(c.V)[:n] for _ in range(c.T)])
+                                         for _ in range(steps)]).astype(np.int32)).to(dev)
+    wsb = hinm.hinm_ocp_sizes(c.M, c.K, c.V, c.Kv, c.dtype, n)
+    work = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    obj = torch.zeros(steps, dtype=torch.float64, device=dev)
+    order = torch.arange(c.M, dtype=torch.int32, device=dev)
+    hinm.hinm_ocp_search(c.M, c.K, c.V, c.Kv, c.dtype, W, None, order, samples, None, n, warmup, obj, work, wsb)
+    torch.cuda.synchronize()
+    order = torch.arange(c.M, dtype=torch.int32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    hinm.hinm_ocp_search(c.M, c.K, c.V, c.Kv, c.dtype, W, None, order, samples, None, n, steps, obj, work, wsb)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms = e0.elapsed_time(e1) / steps
+    o = obj.cpu().numpy()
+    compares = 64.0 * c.T * c.T * c.K
+    out = {"metric": "hinm_ocp_iterations_per_s", "value": round(1e3 / ms, 2), "unit": "iterations/s", "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": round(wall_ms, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": "output-channel permutation search on " + c.name, "tiles": c.T,
+                      "samples_per_tile": n, "clusters": "every tile's own samples",
+                      "pruned_saliency_first_iteration": float(o[0]), "pruned_saliency_last_iteration": float(o[-1])},
+           "gpu_ms_per_iteration": round(ms, 4),
+           "roofline": {"bound": "alu", "kernel": "ocp_cost_kernel", "achieved": None, "peak": FP64_ADD_PEAK_TOPS,
+                        "unit": "T 64-bit compares/s", "frac": None, "traffic": None, "compares_per_launch": compares,
+                        "note": "achieved = compares_per_launch / the kernel's average duration in the rocprofv3 summary"},
+           "cpu_baseline": None}
+    if args.kernel_us:
+        ach = compares / (args.kernel_us * 1e-6) / 1e12
         out["roofline"].update({"achieved": round(ach, 3), "frac": round(ach / FP64_ADD_PEAK_TOPS, 4),
                                 "kernel_us_avg": args.kernel_us})
     print(json.dumps(out))
