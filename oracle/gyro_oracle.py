@@ -17,7 +17,8 @@ What it follows (arXiv 2407.20496):
   * Section 4.1, Eq. 2 and Section 4.2 for the output channels: the partitions are the tiles of V
     output channels; the same number of channels is sampled from every tile, the sampled channels are
     grouped into as many clusters as there are tiles (the paper uses balanced K-means; here the grouping
-    is an input, by default every tile's own samples form a cluster), cost[i][j] (Eq. 4) is the
+    is an input, by default every tile's own samples form a cluster; balanced_kmeans_* below is one
+    reading of that step), cost[i][j] (Eq. 4) is the
     saliency column-vector pruning would remove from tile i's remaining channels plus cluster j, and
     the clusters are assigned to the tiles at minimal total cost.
 
@@ -30,7 +31,12 @@ them is a correct result, and the number of iterations is the caller's.  Output 
 scores of a candidate tile are (sum over the remaining channels in position order) + (sum over the
 cluster's channels in cluster order), each in binary64; the cost is the sum of the K - Kv smallest
 scores (which of several equal scores is pruned does not change it), here added with exact rounding;
-the channels of a cluster fill the slots the tile vacated in position order.
+the channels of a cluster fill the slots the tile vacated in position order.  Balanced K-means
+(the paper only names it): points = the sampled channels' saliency rows, T clusters of exactly n
+points, squared Euclidean distance in binary64 (columns added in ascending order), a round = a
+minimal-cost assignment of points to clusters under the size constraint followed by centroids =
+mean of the members (added in ascending item order, then divided by n); initial centroids = the
+first sample of every tile.  parity unpinned by the paper: it prints no detail of this step.
 
 Pins: tests/test_oracle_gyro.py (brute force over all assignments, the hand-derived example in
 tests/golden/hand_example_icp.txt, cost of the identity assignment = current pruned saliency,
@@ -237,3 +243,72 @@ def ocp_search(W_bits: np.ndarray, dtype: str, rho: Optional[np.ndarray], V: int
         objective[it] = assignment_cost(cost, assign)
         rows = ocp_apply(rows, samples[it], cl, assign)
     return rows.reshape(-1), objective
+
+
+# --------------------------------------------------------------------------
+# Section 4.2, clustering phase: balanced K-means over the sampled output channels
+# --------------------------------------------------------------------------
+
+
+def sampled_features(S: np.ndarray, rows: np.ndarray, sampled: np.ndarray) -> np.ndarray:
+    """float64 [T * n, K]: the saliency row of every sampled channel, item q = sample q % n of tile q // n."""
+    T, n = sampled.shape
+    return np.stack([S[int(rows[q // n, sampled[q // n, q % n]])] for q in range(T * n)])
+
+
+def kmeans_initial_centroids(F: np.ndarray, n: int) -> np.ndarray:
+    """Centroid c starts as the first sample of tile c: float64 [T, K]."""
+    return np.array(F[0::n], copy=True)
+
+
+def kmeans_distances(F: np.ndarray, C: np.ndarray) -> np.ndarray:
+    """d[q, c] = sum_k (F[q, k] - C[c, k])^2, binary64, columns added in ascending order."""
+    Np, K = F.shape
+    d = np.zeros((Np, C.shape[0]), dtype=np.float64)
+    for k in range(K):   # sequential on purpose: pins the rounding order
+        diff = F[:, k][:, None] - C[:, k][None, :]
+        d = d + diff * diff
+    return d
+
+
+def kmeans_balanced_assignment(d: np.ndarray, n: int) -> np.ndarray:
+    """cluster[q] minimising sum_q d[q, cluster[q]] with exactly n points per cluster: a linear assignment of
+    the points to the T * n (cluster, slot) pairs."""
+    rows, cols = linear_sum_assignment(np.repeat(d, n, axis=1))
+    out = np.empty(d.shape[0], dtype=np.int64)
+    out[rows] = cols // n
+    return out
+
+
+def kmeans_centroids(F: np.ndarray, cluster: np.ndarray, T: int, n: int) -> np.ndarray:
+    """Mean of the members: added in ascending item order, then divided by n."""
+    C = np.zeros((T, F.shape[1]), dtype=np.float64)
+    for q in range(F.shape[0]):
+        C[int(cluster[q])] = C[int(cluster[q])] + F[q]
+    return C / float(n)
+
+
+def kmeans_clusters(cluster: np.ndarray, T: int, n: int) -> np.ndarray:
+    """int [T, n]: the items of every cluster in ascending order (the `clusters` input of ocp_cost)."""
+    return np.stack([np.nonzero(np.asarray(cluster) == c)[0] for c in range(T)]).reshape(T, n)
+
+
+def kmeans_objective(d: np.ndarray, cluster: np.ndarray) -> float:
+    total = 0.0
+    for q in range(d.shape[0]):
+        total = total + d[q, int(cluster[q])]
+    return total
+
+
+def balanced_kmeans(F: np.ndarray, n: int, rounds: int, C: Optional[np.ndarray] = None):
+    """Returns (clusters [T, n], centroids [T, K], objective per round)."""
+    T = F.shape[0] // n
+    C = kmeans_initial_centroids(F, n) if C is None else np.array(C, copy=True)
+    cluster = np.arange(F.shape[0]) // n
+    objective = []
+    for _ in range(rounds):
+        d = kmeans_distances(F, C)
+        cluster = kmeans_balanced_assignment(d, n)
+        objective.append(kmeans_objective(d, cluster))
+        C = kmeans_centroids(F, cluster, T, n)
+    return kmeans_clusters(cluster, T, n), C, np.array(objective)

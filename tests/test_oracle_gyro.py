@@ -157,3 +157,47 @@ def test_output_channel_search_never_increases_the_objective():
     assert all(b <= a * (1 + 1e-12) for a, b in zip(seq, seq[1:]))
     end = sum(gyro.vector_pruned_saliency(S[order[t * c.V:(t + 1) * c.V]], c.Kv) for t in range(c.T))
     assert end == pytest.approx(obj[-1], rel=1e-12)
+
+
+# ---- balanced K-means over the sampled channels (one reading of the clustering phase) -------------------
+
+def test_balanced_assignment_is_the_brute_force_minimum():
+    import itertools
+    rng = np.random.default_rng(88)
+    T, n = 3, 2
+    d = rng.integers(0, 30, size=(T * n, T)).astype(np.float64)
+    best = None
+    for labels in set(itertools.permutations([0, 0, 1, 1, 2, 2])):
+        tot = sum(d[q, labels[q]] for q in range(T * n))
+        best = tot if best is None or tot < best else best
+    cluster = gyro.kmeans_balanced_assignment(d, n)
+    assert sorted(np.bincount(cluster, minlength=T).tolist()) == [n] * T
+    assert gyro.kmeans_objective(d, cluster) == best
+
+
+def test_kmeans_recovers_well_separated_groups_and_never_gets_worse():
+    rng = np.random.default_rng(89)
+    T, n, K = 4, 3, 6
+    centres = rng.integers(0, 5, size=(T, K)).astype(np.float64) * 100.0
+    truth = rng.permutation(np.repeat(np.arange(T), n))
+    truth[0::n] = np.arange(T)                 # the first sample of every tile comes from a different group
+    F = centres[truth] + rng.standard_normal((T * n, K))
+    clusters, C, obj = gyro.balanced_kmeans(F, n, 3)
+    for c in range(T):
+        assert len(set(truth[clusters[c]].tolist())) == 1         # every cluster is one of the planted groups
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(obj, obj[1:]))
+    # distances against the textbook expression, centroids against the mean
+    d = gyro.kmeans_distances(F, C)
+    assert np.allclose(d, ((F[:, None, :] - C[None, :, :]) ** 2).sum(axis=2), rtol=1e-12)
+    lab = np.empty(T * n, dtype=np.int64)
+    for c in range(T):
+        lab[clusters[c]] = c
+    assert np.allclose(gyro.kmeans_centroids(F, lab, T, n), np.stack([F[clusters[c]].mean(axis=0) for c in range(T)]))
+
+
+def test_kmeans_with_one_sample_per_tile_keeps_every_point_alone():
+    rng = np.random.default_rng(90)
+    F = rng.standard_normal((5, 7))
+    clusters, C, obj = gyro.balanced_kmeans(F, 1, 2)
+    assert clusters.reshape(-1).tolist() == [0, 1, 2, 3, 4] and obj.tolist() == [0.0, 0.0]
+    assert np.array_equal(C, F)
