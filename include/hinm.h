@@ -192,6 +192,29 @@ hinm_status hinm_ocp_search(const hinm_shape* shape, const void* W, const float*
                             int32_t n_samples, int32_t iters, double* objective,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 4.2, clustering phase of the output-channel search.  The paper names balanced K-means
+ * and gives no detail; this entry point implements one reading, stated here in full.  Points: the
+ * T n_samples channels sampled for one iteration (row_order and samples [T][n_samples] as for
+ * hinm_ocp_search; item q = sample q % n_samples of tile q / n_samples), features: their saliency rows
+ * (rho, or |w|).  T clusters of exactly n_samples points.  A round: squared Euclidean distance of
+ * every point to every centroid in IEEE binary64 (columns added in ascending order, product and sum
+ * rounded separately); the points are assigned to the clusters at minimal total distance under the
+ * size constraint (an exact linear assignment of the points to the (cluster, slot) pairs; which of
+ * several minimal assignments is taken is unspecified); every centroid becomes the sum of its
+ * members' features in ascending item order, divided by n_samples.  centroids, double [T][K] in
+ * device memory, in/out: with init_centroids != 0 they first become the features of the first sample
+ * of every tile.  clusters, int32 [T][n_samples] out: the items of every cluster in ascending order,
+ * the `clusters` argument of hinm_ocp_search.  objective, double [rounds] or NULL: the total distance
+ * reached by each round's assignment; it never increases.  rounds >= 1.  T * n_samples above 1024
+ * returns HINM_ERR_UNSUPPORTED (as do the limits of hinm_ocp_search).  workspace:
+ * hinm_ocp_cluster_sizes bytes, 256-byte aligned. */
+hinm_status hinm_ocp_cluster_sizes(const hinm_shape* shape, int32_t n_samples, size_t* workspace_bytes);
+hinm_status hinm_ocp_cluster(const hinm_shape* shape, const void* W, const float* rho,
+                             const int32_t* row_order, const int32_t* samples, int32_t n_samples,
+                             int32_t rounds, double* centroids, int32_t init_centroids,
+                             int32_t* clusters, double* objective,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* Inverse of hinm_pack: W_out [M][K] = W_HiNM (zeros where pruned).
  * W_out is fully overwritten. */
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx,

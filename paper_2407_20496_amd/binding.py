@@ -38,7 +38,7 @@ def exported_symbols() -> Tuple[str, ...]:
     """Entry points include/hinm.h declares."""
     return ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_pack_scored", "hinm_pack_vectors",
             "hinm_icp_sizes", "hinm_icp_search", "hinm_ocp_sizes", "hinm_ocp_search",
-            "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_prepare_sizes", "hinm_prepare",
+            "hinm_ocp_cluster_sizes", "hinm_ocp_cluster", "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_prepare_sizes", "hinm_prepare",
             "hinm_spmm_prepared_workspace", "hinm_spmm_prepared", "hinm_chain_sizes", "hinm_chain",
             "hinm_status_str", "hinm_version")
 
@@ -75,6 +75,9 @@ def load_library():
     lib.hinm_ocp_sizes.argtypes = [sp, C.c_int32, szp]
     lib.hinm_ocp_search.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.hinm_ocp_cluster_sizes.argtypes = [sp, C.c_int32, szp]
+    lib.hinm_ocp_cluster.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.hinm_unpack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.hinm_spmm.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_uint32, C.c_void_p, C.c_size_t,
@@ -90,7 +93,7 @@ def load_library():
                                        C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
     for name in ("hinm_pack_sizes", "hinm_pack", "hinm_pack_ordered", "hinm_pack_scored", "hinm_pack_vectors",
                  "hinm_icp_sizes", "hinm_icp_search", "hinm_ocp_sizes", "hinm_ocp_search",
-                 "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_chain_sizes", "hinm_chain",
+                 "hinm_ocp_cluster_sizes", "hinm_ocp_cluster", "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_chain_sizes", "hinm_chain",
                  "hinm_prepare_sizes", "hinm_prepare", "hinm_spmm_prepared_workspace", "hinm_spmm_prepared"):
         getattr(lib, name).restype = C.c_int
     lib.hinm_status_str.argtypes = [C.c_int]
@@ -230,6 +233,24 @@ def hinm_ocp_search(M, K, V, Kv, dtype, W, rho, row_order, samples, clusters, n_
     _check(lib.hinm_ocp_search(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(rho), _ptr(row_order), _ptr(samples),
                                _ptr(clusters), int(n_samples), int(iters), _ptr(objective), _ptr(workspace),
                                int(workspace_bytes), _stream(stream)), "hinm_ocp_search")
+
+
+def hinm_ocp_cluster_sizes(M, K, V, Kv, dtype, n_samples) -> int:
+    """Workspace bytes of hinm_ocp_cluster."""
+    lib = load_library()
+    out = C.c_size_t(0)
+    _check(lib.hinm_ocp_cluster_sizes(C.byref(_shape(M, K, V, Kv, dtype)), int(n_samples), C.byref(out)),
+           "hinm_ocp_cluster_sizes")
+    return int(out.value)
+
+
+def hinm_ocp_cluster(M, K, V, Kv, dtype, W, rho, row_order, samples, n_samples, rounds, centroids, init_centroids,
+                     clusters, objective, workspace, workspace_bytes, stream=None) -> None:
+    lib = load_library()
+    _check(lib.hinm_ocp_cluster(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(rho), _ptr(row_order), _ptr(samples),
+                                int(n_samples), int(rounds), _ptr(centroids), int(bool(init_centroids)), _ptr(clusters),
+                                _ptr(objective), _ptr(workspace), int(workspace_bytes), _stream(stream)),
+           "hinm_ocp_cluster")
 
 
 def hinm_unpack(M, K, V, Kv, dtype, vals, nm_idx, vec_idx, W_out, stream=None) -> None:

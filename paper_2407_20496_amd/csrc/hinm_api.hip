@@ -184,6 +184,40 @@ hinm_status hinm_ocp_search(const hinm_shape* shape, const void* W, const float*
   return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 
+static hinm_status check_cluster_shape(const hinm_shape* shape, int32_t n_samples) {
+  hinm_status st = check_ocp_shape(shape, n_samples);
+  if (st != HINM_OK) return st;
+  if ((int64_t)(shape->M / shape->V) * n_samples > kIcpMaxPartitions) return HINM_ERR_UNSUPPORTED;
+  return HINM_OK;
+}
+
+hinm_status hinm_ocp_cluster_sizes(const hinm_shape* shape, int32_t n_samples, size_t* workspace_bytes) {
+  hinm_status st = check_cluster_shape(shape, n_samples);
+  if (st != HINM_OK) return st;
+  if (!workspace_bytes) return HINM_ERR_NULL;
+  *workspace_bytes = kmeans_workspace_layout(*shape, n_samples).total_bytes;
+  return HINM_OK;
+}
+
+hinm_status hinm_ocp_cluster(const hinm_shape* shape, const void* W, const float* rho, const int32_t* row_order,
+                             const int32_t* samples, int32_t n_samples, int32_t rounds, double* centroids,
+                             int32_t init_centroids, int32_t* clusters, double* objective, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  hinm_status st = check_cluster_shape(shape, n_samples);
+  if (st != HINM_OK) return st;
+  if ((!W && !rho) || !row_order || !samples || !centroids || !clusters) return HINM_ERR_NULL;
+  if (rounds < 1) return HINM_ERR_SHAPE;
+  if (!aligned(row_order, 4) || !aligned(samples, 4) || !aligned(clusters, 4) || !aligned(centroids, 8) ||
+      (rho && !aligned(rho, 4)) || (!rho && !aligned(W, 2)) || (objective && !aligned(objective, 8)))
+    return HINM_ERR_SHAPE;
+  const size_t need = kmeans_workspace_layout(*shape, n_samples).total_bytes;
+  if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return HINM_ERR_WORKSPACE;
+  const KmeansArgs a{*shape, W, rho, row_order, samples, n_samples, rounds, centroids, init_centroids != 0,
+                     clusters, objective, workspace};
+  hipError_t e = launch_ocp_cluster(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
 hinm_status hinm_unpack(const hinm_shape* shape, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
                         void* W_out, void* stream) {
   hinm_status st = check_shape(shape);

@@ -138,6 +138,27 @@ struct OcpArgs {
 };
 hipError_t launch_ocp_search(const OcpArgs& a, hipStream_t stream);
 
+// clustering phase of the output-channel search: balanced K-means over the sampled channels
+struct KmeansWorkspace {
+  size_t features, dist, cost, assign, total_bytes;
+};
+KmeansWorkspace kmeans_workspace_layout(const hinm_shape& s, int n_samples);
+struct KmeansArgs {
+  hinm_shape s;
+  const void* W;
+  const float* rho;
+  const int32_t* row_order;  // [M]
+  const int32_t* samples;    // [T][n] positions of one iteration
+  int32_t n_samples;
+  int32_t rounds;            // >= 1
+  double* centroids;         // [T][K], in/out
+  bool init_centroids;       // start from the first sample of every tile instead of the given centroids
+  int32_t* clusters;         // out [T][n]
+  double* objective;         // [rounds] or NULL
+  void* workspace;
+};
+hipError_t launch_ocp_cluster(const KmeansArgs& a, hipStream_t stream);
+
 // ---- device-tuned ("prepared") layer form -------------------------------------------------------------
 hipError_t launch_prepare(const hinm_shape& s, const void* vals, const uint8_t* nm_idx, const int32_t* vec_idx,
                           const int32_t* pi_in, const int32_t* pi_out, void* prepared, hipStream_t stream);

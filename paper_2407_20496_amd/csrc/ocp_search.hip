@@ -167,9 +167,139 @@ __global__ __launch_bounds__(kThreads) void ocp_write_kernel(const int32_t* __re
     row_order[(size_t)i * V + clamp_index(samples[(size_t)i * n + e], V)] = moved[(size_t)i * n + e];
 }
 
+// ---------------------------------------------------------------------------------------------
+// Clustering phase (Section 4.2 names balanced K-means without detail; this is one reading): the
+// T n sampled channels are the points, their saliency rows the features; T clusters of exactly n
+// points.  A round = squared Euclidean distances in binary64 (columns in ascending order, separate
+// multiply and add), a minimal-cost assignment of the points to the T n (cluster, slot) pairs, and
+// centroids = sum of the members in ascending item order, divided by n.
+// ---------------------------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(kThreads) void km_features_kernel(const uint16_t* __restrict__ W,
+                                                               const float* __restrict__ rho,
+                                                               const int32_t* __restrict__ row_order,
+                                                               const int32_t* __restrict__ samples,
+                                                               float* __restrict__ F, int T, int K, int V, int n) {
+  const int q = blockIdx.x;
+  const int k = blockIdx.y * kThreads + threadIdx.x;
+  if (k >= K) return;
+  const int t = q / n, e = q % n;
+  const size_t row = (size_t)clamp_index(row_order[(size_t)t * V + clamp_index(samples[(size_t)t * n + e], V)], T * V);
+  F[(size_t)q * K + k] = (float)saliency_at<DT>(W, rho, row * K + k);
+}
+
+__global__ __launch_bounds__(kThreads) void km_init_kernel(const float* __restrict__ F, double* __restrict__ C, int K,
+                                                           int n) {
+  const int c = blockIdx.x;
+  const int k = blockIdx.y * kThreads + threadIdx.x;
+  if (k < K) C[(size_t)c * K + k] = (double)F[(size_t)c * n * K + k];
+}
+
+// d[q][c], also written n times into the square matrix the assignment solver works on
+__global__ __launch_bounds__(kThreads) void km_distance_kernel(const float* __restrict__ F,
+                                                               const double* __restrict__ C,
+                                                               double* __restrict__ dist, double* __restrict__ cost,
+                                                               int T, int K, int n) {
+#pragma clang fp contract(off)  // product and sum are rounded separately: that rounding is part of the definition
+  const int q = blockIdx.x;
+  const int c = blockIdx.y * kThreads + threadIdx.x;
+  if (c >= T) return;
+  const float* f = F + (size_t)q * K;
+  const double* cen = C + (size_t)c * K;
+  double acc = 0.0;
+  for (int k = 0; k < K; ++k) {
+    const double diff = (double)f[k] - cen[k];
+    const double sq = diff * diff;
+    acc = acc + sq;
+  }
+  dist[(size_t)q * T + c] = acc;
+  double* out = cost + (size_t)q * T * n + (size_t)c * n;
+  for (int s = 0; s < n; ++s) out[s] = acc;
+}
+
+// new centroids from the assignment (point q belongs to cluster assign[q] / n); block (0, 0) also
+// reports the sum of the distances of the points to the centroids they were assigned to
+__global__ __launch_bounds__(kThreads) void km_update_kernel(const float* __restrict__ F,
+                                                             const int32_t* __restrict__ assign,
+                                                             const double* __restrict__ dist, double* __restrict__ C,
+                                                             double* __restrict__ objective, int T, int K, int n) {
+  const int c = blockIdx.x;
+  const int k = blockIdx.y * kThreads + threadIdx.x;
+  const int points = T * n;
+  if (k < K) {
+    double acc = 0.0;
+    for (int q = 0; q < points; ++q)
+      if (clamp_index(assign[q], points) / n == c) acc += (double)F[(size_t)q * K + k];
+    C[(size_t)c * K + k] = acc / (double)n;
+  }
+  if (objective && c == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    double total = 0.0;
+    for (int q = 0; q < points; ++q) total += dist[(size_t)q * T + clamp_index(assign[q], points) / n];
+    *objective = total;
+  }
+}
+
+// clusters[c] = its items in ascending order
+__global__ __launch_bounds__(kThreads) void km_clusters_kernel(const int32_t* __restrict__ assign,
+                                                               int32_t* __restrict__ clusters, int T, int n) {
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= T) return;
+  const int points = T * n;
+  int filled = 0;
+  for (int q = 0; q < points && filled < n; ++q)
+    if (clamp_index(assign[q], points) / n == c) clusters[(size_t)c * n + filled++] = q;
+  for (; filled < n; ++filled) clusters[(size_t)c * n + filled] = c * n + filled;  // only after a malformed assignment
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }  // namespace
+
+KmeansWorkspace kmeans_workspace_layout(const hinm_shape& s, int n_samples) {
+  const size_t T = s.M / s.V, points = T * (size_t)n_samples;
+  KmeansWorkspace w;
+  size_t off = 0;
+  w.features = off; off += align256(points * s.K * sizeof(float));
+  w.dist = off;     off += align256(points * T * sizeof(double));
+  w.cost = off;     off += align256(points * points * sizeof(double));
+  w.assign = off;   off += align256(points * sizeof(int32_t));
+  w.total_bytes = off;
+  return w;
+}
+
+hipError_t launch_ocp_cluster(const KmeansArgs& a, hipStream_t stream) {
+  const hinm_shape& s = a.s;
+  const int T = s.M / s.V, n = a.n_samples, points = T * n;
+  const KmeansWorkspace w = kmeans_workspace_layout(s, n);
+  uint8_t* ws = static_cast<uint8_t*>(a.workspace);
+  float* F = reinterpret_cast<float*>(ws + w.features);
+  double* dist = reinterpret_cast<double*>(ws + w.dist);
+  double* cost = reinterpret_cast<double*>(ws + w.cost);
+  int32_t* assign = reinterpret_cast<int32_t*>(ws + w.assign);
+  const uint16_t* Wb = static_cast<const uint16_t*>(a.W);
+  const int k_blocks = (s.K + kThreads - 1) / kThreads;
+  if (s.dtype == HINM_F16)
+    km_features_kernel<HINM_F16><<<dim3(points, k_blocks), kThreads, 0, stream>>>(Wb, a.rho, a.row_order, a.samples, F, T,
+                                                                                   s.K, s.V, n);
+  else
+    km_features_kernel<HINM_BF16><<<dim3(points, k_blocks), kThreads, 0, stream>>>(Wb, a.rho, a.row_order, a.samples, F,
+                                                                                    T, s.K, s.V, n);
+  if (a.init_centroids) km_init_kernel<<<dim3(T, k_blocks), kThreads, 0, stream>>>(F, a.centroids, s.K, n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  for (int r = 0; r < a.rounds; ++r) {
+    km_distance_kernel<<<dim3(points, (T + kThreads - 1) / kThreads), kThreads, 0, stream>>>(F, a.centroids, dist, cost,
+                                                                                             T, s.K, n);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_assignment(cost, assign, 1, points, stream);
+    if (e != hipSuccess) return e;
+    km_update_kernel<<<dim3(T, k_blocks), kThreads, 0, stream>>>(F, assign, dist, a.centroids,
+                                                                 a.objective ? a.objective + r : nullptr, T, s.K, n);
+  }
+  km_clusters_kernel<<<(T + kThreads - 1) / kThreads, kThreads, 0, stream>>>(assign, a.clusters, T, n);
+  return hipGetLastError();
+}
 
 OcpWorkspace ocp_workspace_layout(const hinm_shape& s, int n_samples) {
   const size_t T = s.M / s.V;

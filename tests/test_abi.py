@@ -106,6 +106,13 @@ def test_null_and_workspace_errors_are_reported_before_any_launch():
     assert lib.hinm_ocp_search(C.byref(sh), fake, None, fake, fake + 2, None, 4, 1, None, fake, 1 << 30, None) == 2
     many = binding._Shape(32768, 64, 16, 32, 0)                                # 2048 tiles
     assert lib.hinm_ocp_sizes(C.byref(many), 1, C.byref(need)) == 5
+    # clustering: the point count limit, rounds, nulls
+    assert lib.hinm_ocp_cluster_sizes(C.byref(sh), 4, C.byref(need)) == 0 and need.value > 0
+    big_t = binding._Shape(16384, 64, 16, 32, 0)                               # 1024 tiles x 2 samples > 1024 points
+    assert lib.hinm_ocp_cluster_sizes(C.byref(big_t), 2, C.byref(need)) == 5
+    assert lib.hinm_ocp_cluster(C.byref(sh), fake, None, fake, fake, 4, 0, fake, 1, fake, None, fake, 1 << 30, None) == 2
+    assert lib.hinm_ocp_cluster(C.byref(sh), fake, None, fake, fake, 4, 1, None, 1, fake, None, fake, 1 << 30, None) == 1
+    assert lib.hinm_ocp_cluster(C.byref(sh), fake, None, fake, fake, 4, 1, fake, 1, fake, None, None, 0, None) == 4
     # spmm: null X, bad N, bad ld, misaligned X, unknown flag, two kernels forced
     args = dict(N=64, vals=fake, nm=fake, vec=fake, X=fake, ldx=64, Y=fake, ldy=64, flags=0)
 

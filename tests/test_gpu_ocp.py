@@ -122,3 +122,76 @@ def test_c2_layer_one_iteration():
     start = np.arange(c.M, dtype=np.int32)
     after, obj = _gpu_search(c, Wb, None, start, samples, clusters)
     _check_iteration(c, S, start, after, samples[0], clusters[0], obj[0], exact=False)
+
+
+# ---- clustering phase: balanced K-means over the sampled channels -----------------------------------------
+
+def _gpu_cluster(c, Wb, rho, row_order, sampled, rounds, centroids=None):
+    import torch
+    import paper_2407_20496_amd as hinm
+    from tests import gpu_util as gu
+    T, n = sampled.shape
+    wsb = hinm.hinm_ocp_cluster_sizes(c.M, c.K, c.V, c.Kv, c.dtype, n)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=gu.DEV)
+    cen = (torch.full((T, c.K), float("nan"), dtype=torch.float64, device=gu.DEV) if centroids is None
+           else torch.from_numpy(np.ascontiguousarray(centroids)).to(gu.DEV))
+    clusters = torch.full((T, n), -1, dtype=torch.int32, device=gu.DEV)
+    obj = torch.full((rounds,), float("nan"), dtype=torch.float64, device=gu.DEV)
+    hinm.hinm_ocp_cluster(c.M, c.K, c.V, c.Kv, c.dtype, gu.dev_bits(Wb), None if rho is None else gu.dev_f32(rho),
+                          gu.dev_i32(row_order), gu.dev_i32(sampled), n, rounds, cen, centroids is None, clusters, obj,
+                          ws, wsb)
+    torch.cuda.synchronize()
+    return clusters.cpu().numpy(), cen.cpu().numpy(), obj.cpu().numpy()
+
+
+@pytest.mark.parametrize("M,K,V,Kv,n,dtype,scored", [
+    (48, 40, 8, 16, 3, "f16", False),
+    (64, 300, 16, 152, 5, "bf16", True),
+    (40, 24, 1, 8, 1, "f16", True),
+])
+def test_balanced_kmeans_round_by_round(M, K, V, Kv, n, dtype, scored):
+    c = synth.small_case(M, K, V, Kv, 1, dtype, 101)
+    Wb = c.weights()
+    rng = np.random.default_rng(102)
+    rho = (rng.standard_normal((M, K)) ** 2).astype(np.float32) if scored else None
+    S = gyro.saliency_matrix(Wb, dtype, rho)
+    row_order = rng.permutation(M).astype(np.int32)
+    sampled = np.stack([rng.permutation(V)[:n] for _ in range(c.T)]).astype(np.int32)
+    F = gyro.sampled_features(S, row_order.reshape(c.T, V), sampled)
+    cen, trace = None, []
+    for r in range(3):
+        start = gyro.kmeans_initial_centroids(F, n) if cen is None else cen
+        clusters, cen_new, obj = _gpu_cluster(c, Wb, rho, row_order, sampled, 1, cen)
+        assert sorted(clusters.reshape(-1).tolist()) == list(range(c.T * n))          # every item once: n per cluster
+        assert all(clusters[k].tolist() == sorted(clusters[k].tolist()) for k in range(c.T))
+        label = np.empty(c.T * n, dtype=np.int64)
+        for k in range(c.T):
+            label[clusters[k]] = k
+        d = gyro.kmeans_distances(F, start)
+        assert obj[0] == gyro.kmeans_objective(d, label)                               # same distances, same order
+        best = gyro.kmeans_objective(d, gyro.kmeans_balanced_assignment(d, n))
+        assert obj[0] <= best * (1 + 1e-9) + 1e-300
+        assert np.array_equal(cen_new, gyro.kmeans_centroids(F, label, c.T, n))
+        trace.append(obj[0])
+        cen = cen_new
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(trace, trace[1:]))
+    # three rounds in one call: the same clusters, centroids and objectives
+    clusters3, cen3, obj3 = _gpu_cluster(c, Wb, rho, row_order, sampled, 3, None)
+    assert np.array_equal(clusters3, clusters) and np.array_equal(cen3, cen) and np.array_equal(obj3, np.array(trace))
+
+
+def test_clusters_feed_the_search_on_the_c2_layer():
+    c = synth.c2()
+    Wb = c.weights()
+    rng = np.random.default_rng(103)
+    S = gyro.saliency_matrix(Wb, c.dtype, None)
+    n = 8
+    sampled = np.stack([rng.permutation(c.V)[:n] for _ in range(c.T)]).astype(np.int32)
+    start = np.arange(c.M, dtype=np.int32)
+    clusters, cen, obj = _gpu_cluster(c, Wb, None, start, sampled, 2, None)
+    assert sorted(clusters.reshape(-1).tolist()) == list(range(c.T * n)) and obj[1] <= obj[0]
+    F = gyro.sampled_features(S, start.reshape(c.T, c.V), sampled)
+    d0 = gyro.kmeans_distances(F, gyro.kmeans_initial_centroids(F, n))
+    assert obj[0] <= gyro.kmeans_objective(d0, gyro.kmeans_balanced_assignment(d0, n)) * (1 + 1e-9)
+    after, sobj = _gpu_search(c, Wb, None, start, sampled[None], clusters[None].astype(np.int32))
+    _check_iteration(c, S, start, after, sampled, clusters, sobj[0], exact=False)
