@@ -43,7 +43,7 @@ PACK_WORKLOADS = ("pack-c5", "pack-c5-ordered", "pack-c5-scored", "pack-c5-vecto
 
 SWEEP_WORKLOADS = ("sweep-bert", "sweep-resnet")
 ICP_WORKLOADS = ("icp-c2", "icp-c4")
-OCP_WORKLOADS = ("ocp-c2", "ocp-c5")
+OCP_WORKLOADS = ("ocp-c2", "ocp-c5", "ocp-cluster-c2")
 FP64_ADD_PEAK_TOPS = 39.3         # 256 compute units x 64 lanes x 2.4 GHz = half the fp64 FMA flop figure
 
 
@@ -575,7 +575,7 @@ def bench_ocp(args, torch, hinm, dev):
     drawn on the host from a seeded generator, every tile's own samples as its cluster.  `value` = iterations
     per second; the roofline object prices the cost kernel (64 counting passes of 64-bit compares over the K
     column scores of every tile x cluster pair) against the 64-bit rate of the vector units."""
-    c = synth.c2() if args.workload == "ocp-c2" else synth.c5()
+    c = synth.c5() if args.workload == "ocp-c5" else synth.c2()
     n = max(1, c.V // 8)
     W = torch.from_numpy(c.weights().view(np.int16)).to(dev)
     steps = args.steps or 10
@@ -583,6 +583,36 @@ def bench_ocp(args, torch, hinm, dev):
     rng = np.random.default_rng(20496)
     samples = torch.from_numpy(np.stack([np.stack([rng.permutation(c.V)[:n] for _ in range(c.T)])
                                          for _ in range(steps)]).astype(np.int32)).to(dev)
+    if args.workload == "ocp-cluster-c2":
+        # the clustering phase alone: K rounds of balanced K-means over one iteration's samples
+        wsb = hinm.hinm_ocp_cluster_sizes(c.M, c.K, c.V, c.Kv, c.dtype, n)
+        work = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        order = torch.arange(c.M, dtype=torch.int32, device=dev)
+        cen = torch.empty((c.T, c.K), dtype=torch.float64, device=dev)
+        clusters = torch.empty((c.T, n), dtype=torch.int32, device=dev)
+        obj = torch.zeros(steps, dtype=torch.float64, device=dev)
+        hinm.hinm_ocp_cluster(c.M, c.K, c.V, c.Kv, c.dtype, W, None, order, samples[0], n, 1, cen, True, clusters, obj,
+                              work, wsb)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        hinm.hinm_ocp_cluster(c.M, c.K, c.V, c.Kv, c.dtype, W, None, order, samples[0], n, steps, cen, True, clusters,
+                              obj, work, wsb)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        ms = e0.elapsed_time(e1) / steps
+        o = obj.cpu().numpy()
+        print(json.dumps({
+            "metric": "hinm_ocp_cluster_rounds_per_s", "value": round(1e3 / ms, 2), "unit": "rounds/s", "n_gpus": 1,
+            "steps": steps, "warmup": 1, "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": "balanced K-means over the sampled channels of " + c.name, "points": c.T * n,
+                       "clusters": c.T, "features": c.K, "distance_first_round": float(o[0]),
+                       "distance_last_round": float(o[-1])},
+            "gpu_ms_per_round": round(ms, 4), "roofline": None, "cpu_baseline": None}))
+        return
     wsb = hinm.hinm_ocp_sizes(c.M, c.K, c.V, c.Kv, c.dtype, n)
     work = torch.empty(wsb, dtype=torch.uint8, device=dev)
     obj = torch.zeros(steps, dtype=torch.float64, device=dev)
