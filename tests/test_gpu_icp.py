@@ -65,6 +65,7 @@ def test_hand_example_on_gpu():
     (64, 200, 16, 104, "bf16", True),       # 26 partitions
     (96, 1200, 32, 1032, "f16", True),      # 258 partitions: more than one column per thread in the solver
     (16, 64, 1, 64, "bf16", False),         # single-row tiles
+    (8, 4200, 4, 4096, "f16", True),        # 1024 partitions: the largest tile the solver takes
 ])
 def test_every_iteration_against_the_oracle(M, K, V, Kv, dtype, scored):
     c = synth.small_case(M, K, V, Kv, 1, dtype, 90)
