@@ -134,10 +134,82 @@ __global__ __launch_bounds__(THREADS) void icp_assign_kernel(const double* __res
     v[j] = 0.0;
     p[j] = 0;
     way[j] = 0;
+    used[j] = 0;  // until the main loop: "row j is matched"
   }
   __syncthreads();
+  // Start from feasible potentials and a greedy partial matching instead of from nothing: v[j] = the
+  // smallest cost in column j, u[i] = the smallest reduced cost in row i, and row i takes the column
+  // where that minimum sits (the lowest one) if it is still free.  Most rows are matched here, with n
+  // reductions; only the others need an augmenting path (up to n reductions each).
+  {
+    const double* m = IN_LDS ? cost_lds : a;
+    for (int j = 1 + tid; j <= n; j += THREADS) {
+      double lo = kInf;
+      for (int i = 0; i < n; ++i) {
+        const double x = m[(size_t)i * n + (j - 1)];
+        lo = x < lo ? x : lo;
+      }
+      v[j] = lo < kInf ? lo : 0.0;
+    }
+    __syncthreads();
+    for (int i = 1; i <= n; ++i) {
+      const double* arow = m + (size_t)(i - 1) * n;
+      double best = kInf;
+      int best_j = n + 1;
+      for (int j = 1 + tid; j <= n; j += THREADS) {
+        const double x = arow[j - 1] - v[j];
+        if (x < best) {
+          best = x;
+          best_j = j;
+        }
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const double ob = __shfl_down(best, off);
+        const int oj = __shfl_down(best_j, off);
+        if (ob < best || (ob == best && oj < best_j)) {
+          best = ob;
+          best_j = oj;
+        }
+      }
+      if (lane == 0) {
+        red_val[wave] = best;
+        red_idx[wave] = best_j;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        double lo = red_val[0];
+        int at = red_idx[0];
+        for (int w = 1; w < THREADS / 64; ++w)
+          if (red_val[w] < lo || (red_val[w] == lo && red_idx[w] < at)) {
+            lo = red_val[w];
+            at = red_idx[w];
+          }
+        if (lo < kInf && at <= n) {
+          u[i] = lo;
+          if (p[at] == 0) {
+            p[at] = i;
+            used[i] = 1;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // rows still to be matched, in ascending order
+  __shared__ int free_list[MAXN];
+  __shared__ int n_free;
+  if (tid == 0) {
+    int count = 0;
+    for (int i = 1; i <= n; ++i)
+      if (!used[i]) free_list[count++] = i;
+    n_free = count;
+  }
+  __syncthreads();
+  const int free_rows = n_free;
   bool failed = false;
-  for (int i = 1; i <= n && !failed; ++i) {
+  for (int f = 0; f < free_rows && !failed; ++f) {
+    const int i = free_list[f];
     if (tid == 0) p[0] = i;
     for (int j = tid; j <= n; j += THREADS) {
       minv[j] = kInf;
