@@ -14,6 +14,7 @@
 // The arrangement is tracked as a permutation of the slots of the incoming vector index, so the
 // saliencies are gathered from W (or rho) only once.
 #include "hinm_internal.h"
+#include "wave_reduce.h"
 
 namespace hinm {
 namespace {
@@ -104,46 +105,6 @@ __global__ __launch_bounds__(kThreads) void icp_cost_kernel(const float* __restr
     for (int e = 0; e < kCostRowsPerThread; ++e)
       if (i0 + e < P) cost[((size_t)t * P + i0 + e) * P + j] = acc[e];
   }
-}
-
-// Wave-wide minimum with data-parallel-primitive moves instead of LDS shuffles: four shifts inside
-// every row of 16 lanes, then lane 15 of a row into the next row, then lane 31 into the upper half;
-// lane 63 ends up with the minimum of all 64 lanes and is read back as a wave-uniform value.  Lanes
-// that a step does not write keep their own value, which is harmless for a minimum.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ int dpp_move(int own) {
-  return __builtin_amdgcn_update_dpp(own, own, CTRL, ROW_MASK, 0xf, false);
-}
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ double dpp_move(double own) {
-  const int lo = dpp_move<CTRL, ROW_MASK>(__double2loint(own));
-  const int hi = dpp_move<CTRL, ROW_MASK>(__double2hiint(own));
-  return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ double wave_min(double v) {
-  v = __builtin_fmin(v, dpp_move<0x111, 0xf>(v));  // row_shr:1
-  v = __builtin_fmin(v, dpp_move<0x112, 0xf>(v));  // row_shr:2
-  v = __builtin_fmin(v, dpp_move<0x114, 0xf>(v));  // row_shr:4
-  v = __builtin_fmin(v, dpp_move<0x118, 0xf>(v));  // row_shr:8
-  v = __builtin_fmin(v, dpp_move<0x142, 0xa>(v));  // row_bcast:15 into rows 1 and 3
-  v = __builtin_fmin(v, dpp_move<0x143, 0xc>(v));  // row_bcast:31 into rows 2 and 3
-  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63),
-                          __builtin_amdgcn_readlane(__double2loint(v), 63));
-}
-__device__ __forceinline__ int wave_min(int v) {
-  v = min(v, dpp_move<0x111, 0xf>(v));
-  v = min(v, dpp_move<0x112, 0xf>(v));
-  v = min(v, dpp_move<0x114, 0xf>(v));
-  v = min(v, dpp_move<0x118, 0xf>(v));
-  v = min(v, dpp_move<0x142, 0xa>(v));
-  v = min(v, dpp_move<0x143, 0xc>(v));
-  return __builtin_amdgcn_readlane(v, 63);
-}
-// (smallest value, lowest index among the lanes that hold it) over the wave, wave-uniform
-__device__ __forceinline__ void wave_argmin(double& best, int& best_j, int none) {
-  const double lo = wave_min(best);
-  best_j = wave_min(best == lo ? best_j : none);
-  best = lo;
 }
 
 // Linear assignment by shortest augmenting paths (rows = partitions, columns = samples), one
