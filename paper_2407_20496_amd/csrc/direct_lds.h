@@ -15,6 +15,11 @@ __device__ __forceinline__ void copy16_to_lds(const void* src_lane, void* lds_wa
   __builtin_amdgcn_global_load_lds((global_void_t*)src_lane, (lds_void_t*)lds_wave_base, 16, 0, 0);
 }
 
+__device__ __forceinline__ void copy4_to_lds(const void* src_lane, void* lds_wave_base) {
+  // every lane copies 4 bytes; lane l lands at lds_wave_base + 4 l
+  __builtin_amdgcn_global_load_lds((global_void_t*)src_lane, (lds_void_t*)lds_wave_base, 4, 0, 0);
+}
+
 // s_waitcnt vmcnt(n) with everything else left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
 // expcnt 6:4, lgkmcnt 11:8)
 template <int N>

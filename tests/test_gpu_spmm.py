@@ -70,6 +70,8 @@ def _check_full(case, N, flags_list, relu=False, identity=False, ld_pad=0):
     (384, 512, 128, 256, 264),
     (192, 256, 96, 64, 40),
     (64, 200, 16, 72, 19),         # Kv % 64 != 0: k tail
+    (4096, 256, 32, 128, 1030),    # enough tiles for the 512-column blocks of the direct-to-LDS tile kernel
+    (1536, 384, 96, 192, 1100),    # 96-row tiles, several stages, 256-column blocks
 ])
 def test_spmm_small_all_kernels(M, K, V, Kv, N, dtype):
     case = synth.small_case(M, K, V, Kv, N, dtype, 60)
