@@ -262,7 +262,8 @@ def main():
                               "spmm_panel_prepared_kernel" if (panel_fits and args.variant in (0, 15)) else
                               "spmm_tile_prepared_kernel")
     else:
-        roofline["kernel"] = "spmm_skinny_kernel" if N <= 16 or c.V % 32 else "spmm_tile_kernel"
+        roofline["kernel"] = ("spmm_skinny_kernel" if N <= 16 or c.V % 32 else
+                              "spmm_tile_dma_kernel" if c.Kv % 64 == 0 else "spmm_tile_kernel")
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
