@@ -258,7 +258,8 @@ def main():
     if use_prepared:
         k8 = (c.K + 7) // 8 * 8
         panel_fits = (k8 + 8) * 128 + 8 * 32 * 144 <= 160 * 1024
-        roofline["kernel"] = ("spmm_skinny_prepared_kernel" if N <= 32 else
+        roofline["kernel"] = ("spmm_rows16_prepared_kernel" if (N <= 16 and args.variant in (0, 11)) else
+                              "spmm_skinny_prepared_kernel" if N <= 32 else
                               "spmm_panel_prepared_kernel" if (panel_fits and args.variant in (0, 15)) else
                               "spmm_tile_prepared_kernel")
     else:

@@ -394,12 +394,17 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
   PreparedArgs a{*shape, N, prepared, X, ldx, Y, ldy, (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0,
                  (int)((flags & HINM_VARIANT_MASK) >> HINM_VARIANT_SHIFT), workspace, workspace_bytes};
   hipError_t e;
-  if (N <= 32 && a.tile_variant == 0) {
+  // up to 16 columns: 16-row workgroups on the 16x16x64 form (measured faster than the 32-row kernel on every
+  // decode shape tried, by 8-10 % with 344 row blocks of 32 and by 15-37 % with 128); variant 11 pins it for any N
+  if (a.tile_variant == 11 || (a.tile_variant == 0 && N <= 16)) {
+    if ((N + 15) / 16 > 65535) return HINM_ERR_UNSUPPORTED;
+    e = launch_spmm_rows16_prepared(a, stream);
+  } else if (N <= 32 && (a.tile_variant == 0 || a.tile_variant == 12)) {  // variant 12 pins the 32-row skinny kernel
     const size_t need = skinny_prepared_workspace_bytes(*shape, N);
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned(workspace, 256))) return HINM_ERR_WORKSPACE;
     e = launch_spmm_skinny_prepared(a, stream);
   } else {
-    if (N == 1 || ldx % 8 != 0 || ldy % 8 != 0) return HINM_ERR_UNSUPPORTED;
+    if (N == 1 || ldx % 8 != 0 || ldy % 8 != 0 || a.tile_variant == 12) return HINM_ERR_UNSUPPORTED;
     const bool panel = (a.tile_variant == 15) || (a.tile_variant == 0 && spmm_panel_prepared_preferred(a));
     if (panel && !spmm_panel_prepared_supported(a)) return HINM_ERR_UNSUPPORTED;
     e = panel ? launch_spmm_panel_prepared(a, stream) : launch_spmm_tile_prepared(a, stream);

@@ -186,5 +186,7 @@ hipError_t launch_spmm_panel_prepared(const PreparedArgs& a, hipStream_t stream)
 // few columns (N <= 32): whole-tile workgroups, kept columns split over workgroups
 size_t skinny_prepared_workspace_bytes(const hinm_shape& s, int N);
 hipError_t launch_spmm_skinny_prepared(const PreparedArgs& a, hipStream_t stream);
+// few columns and few tiles: 16-row workgroups on the 16x16x64 form, reading the same prepared blocks
+hipError_t launch_spmm_rows16_prepared(const PreparedArgs& a, hipStream_t stream);
 
 }  // namespace hinm

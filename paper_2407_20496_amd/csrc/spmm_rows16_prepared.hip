@@ -1,0 +1,229 @@
+// HiNM product for few columns from the device-tuned layer form, 16 output channels per workgroup
+// (arXiv 2407.20496, Section 3.2; layout in prepared_layout.h).
+//
+// spmm_skinny_prepared_kernel gives every workgroup a 32-row block of a tile; a layer with few tiles
+// (4096 rows at V = 128: 128 blocks) then leaves half of the 256 compute units idle.  This kernel
+// halves the granularity: one workgroup owns 16 rows and a block of 16 columns and uses the 16x16x64
+// sparse MFMA, whose A operand for lane (row i, lane group q) is exactly the 16 bytes the prepared
+// block holds for lane 32 (q % 2) + i of substep q / 2 -- so the prepared form is read in place, four
+// contiguous 256-byte segments per step.  Otherwise it works like the canonical-array kernel for few
+// columns: the waves split the tile's steps into contiguous ranges, every wave issues all loads of a
+// batch of steps before it uses the first, gathered rows pass through a private LDS slab and come
+// back transposed, and the per-wave partial tiles are added in a fixed order through LDS.
+#include "hinm_internal.h"
+#include "mfma_types.h"
+#include "prepared_layout.h"
+
+namespace hinm {
+namespace {
+
+constexpr int kRows = 16;   // rows per workgroup
+constexpr int kCols = 16;   // columns per workgroup
+constexpr int kStep = 64;   // kept columns per MFMA
+// private LDS slab of one wave: 64 rows x 16 columns, 8-row blocks padded so that the four lane
+// groups of a transposing read fall on different banks
+constexpr int kSlabBytes = 8 * 384;
+
+__device__ __forceinline__ int slab_row_offset(int row) { return row * 32 + (row >> 3) * 128; }
+
+__device__ __forceinline__ void wave_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// B operand of one step from the wave's slab: slots 8 h + 4 u .. + 3 of lane group q hold rows
+// 32 h + 8 q + 4 u + (0..3) at column i; inside a 16-lane group lane i addresses row (i / 4) and
+// columns 4 (i % 4) .. + 3.
+__device__ __forceinline__ u32x8 read_b_operand(const uint8_t* slab, int i, int q) {
+  u32x8 b;
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int row = 32 * h + 8 * q + 4 * u + (i >> 2);
+      const u32x2 v = lds_read_tr16(slab + slab_row_offset(row) + (i & 3) * 8);
+      b[(2 * h + u) * 2] = v.x;
+      b[(2 * h + u) * 2 + 1] = v.y;
+    }
+  return b;
+}
+
+// XMODE: 0 = any N / ld (element loads, slow), 1 = the 16 columns are inside N and rows are
+// 16-byte aligned, 2 = N == 1.  KB = steps whose loads are issued together.
+template <int DT, int NW, int XMODE, int KB>
+__global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
+    const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
+    const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
+    int V, int RB, int S64, int N, bool relu, bool out_f32) {
+  constexpr int RBW = 1;
+  __shared__ __attribute__((aligned(16))) uint8_t slab_all[NW * kSlabBytes];
+  static_assert(RBW * kRows * kCols * 4 <= kSlabBytes, "partial tiles must fit the slab");
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int row0 = blockIdx.x * kRows;  // first row of the layer handled here
+  const int t = row0 / V;
+  const int rb32 = (row0 % V) / 32;     // 32-row block of the prepared form that holds these rows
+  const int hf = (row0 % 32) / 16;      // ... and which half of it
+  const int n0 = blockIdx.y * kCols;
+  const int per_wave = (S64 + NW - 1) / NW;
+  const int s_begin = wave * per_wave;
+  const int s_end = min(S64, s_begin + per_wave);  // this wave's contiguous range of steps (all steps are full: padded)
+
+  uint8_t* slab = slab_all + wave * kSlabBytes;
+  const int i = lane & 15;   // A row / B column inside the block
+  const int q = lane >> 4;   // lane group: groups 4 q .. 4 q + 3 of the step = substep q / 2, quad q % 2
+  // this lane's 16 bytes inside a (tile, step, row block) block of the prepared form, and its index word
+  const int lane32 = 32 * (q & 1) + 16 * hf + i;
+  const uint8_t* a_lane = prep_blocks + ((size_t)t * S64 * RB + rb32) * kPrepBlockBytes + (q >> 1) * 1024 + lane32 * 16;
+  const uint8_t* idx_lane = prep_blocks + ((size_t)t * S64 * RB + rb32) * kPrepBlockBytes + kPrepIdxOffset + lane32 * 4;
+  const size_t step_stride = (size_t)RB * kPrepBlockBytes;
+  const int32_t* gt = gather + (size_t)t * S64 * 64;
+
+  // output rows of the epilogue, fetched early: element e = threadIdx.x + k * blockDim.x
+  constexpr int kOutPerThread = (RBW * kRows * kCols + NW * 64 - 1) / (NW * 64);
+  int64_t out_row[kOutPerThread];
+#pragma unroll
+  for (int k = 0; k < kOutPerThread; ++k) {
+    const int e = threadIdx.x + k * NW * 64;
+    const int row = min(e / kCols, RBW * kRows - 1);
+    out_row[k] = out_rows[row0 + row];
+  }
+
+  f32x4 acc[RBW];
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int sb = s_begin; sb < s_end; sb += KB) {
+    u32x4 a_reg[KB][RBW];
+    int idx_reg[KB][RBW];
+    int col[KB];
+    u32x4 b_lo[KB], b_hi[KB];
+    // Loads come back in issue order: the gather-table entries go first, the bulk weight stream is issued
+    // behind them, and the input rows are requested as soon as their indices are known and arrive while the
+    // weights are still streaming.  (Steps past the wave's range are clamped to its last step and zeroed
+    // before use.)
+    // phase 1: gather-table entries (vector index composed with the input-channel order; -1 = padding)
+#pragma unroll
+    for (int u = 0; u < KB; ++u) col[u] = gt[kStep * min(sb + u, s_end - 1) + lane];
+    __builtin_amdgcn_sched_barrier(0);
+    // phase 2: stored values and NM nibbles, 16 bytes + one index word per lane and step
+#pragma unroll
+    for (int u = 0; u < KB; ++u) {
+      const size_t off = (size_t)min(sb + u, s_end - 1) * step_stride;
+      a_reg[u][0] = *reinterpret_cast<const u32x4*>(a_lane + off);
+      const uint32_t word = *reinterpret_cast<const uint32_t*>(idx_lane + off);
+      idx_reg[u][0] = (int)((q >> 1) ? (word >> 16) : (word & 0xFFFFu));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // phase 3: input rows, 16 columns wide
+#pragma unroll
+    for (int u = 0; u < KB; ++u) {
+      const uint16_t* xr = (col[u] >= 0) ? X + (size_t)col[u] * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
+      if constexpr (XMODE == 1) {
+        b_lo[u] = *reinterpret_cast<const u32x4*>(xr);
+        b_hi[u] = *reinterpret_cast<const u32x4*>(xr + 8);
+      } else if constexpr (XMODE == 2) {
+        b_lo[u] = u32x4{(uint32_t)xr[0], 0, 0, 0};
+        b_hi[u] = u32x4{0, 0, 0, 0};
+      } else {
+        uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (n0 + e < N) w[e >> 1] |= (uint32_t)xr[e] << (16 * (e & 1));
+        b_lo[u] = u32x4{w[0], w[1], w[2], w[3]};
+        b_hi[u] = u32x4{w[4], w[5], w[6], w[7]};
+      }
+    }
+    // phase 4: multiply
+#pragma unroll
+    for (int u = 0; u < KB; ++u) {
+      const bool live = sb + u < s_end;  // wave-uniform
+      uint8_t* wr = slab + slab_row_offset(lane);
+      *reinterpret_cast<u32x4*>(wr) = b_lo[u];
+      *reinterpret_cast<u32x4*>(wr + 16) = b_hi[u];
+      wave_sync_lds();
+      u32x8 b = read_b_operand(slab, i, q);
+      if (!live) b = u32x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        const u32x4 a = live ? a_reg[u][rb] : u32x4{0, 0, 0, 0};
+        acc[rb] = smfmac_16x16x64<DT, 0>(a, b, acc[rb], idx_reg[u][rb]);
+      }
+      wave_sync_lds();
+    }
+  }
+
+  // ---- fixed-order reduction over the waves, epilogue ---------------------------------------
+  // D layout: lane holds column lane % 16, rows 4 * (lane / 16) + reg.
+  // (the slab is free now; its first kilobytes take this wave's partial tiles)
+  wave_sync_lds();
+  float* partial = reinterpret_cast<float*>(slab);
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+    for (int reg = 0; reg < 4; ++reg) partial[(16 * rb + 4 * q + reg) * kCols + i] = acc[rb][reg];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kOutPerThread; ++k) {
+    const int e = threadIdx.x + k * NW * 64;
+    if (e < RBW * kRows * kCols) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) sum += reinterpret_cast<const float*>(slab_all + w * kSlabBytes)[e];
+      if (relu) sum = sum > 0.f ? sum : 0.f;
+      const int c = e % kCols;
+      if (n0 + c < N) {
+        if (out_f32) static_cast<float*>(Y)[out_row[k] * ldy + n0 + c] = sum;
+        else static_cast<uint16_t*>(Y)[out_row[k] * ldy + n0 + c] = float_to_bits<DT>(sum);
+      }
+    }
+  }
+}
+
+template <int DT, int NW, int KB>
+void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t stream) {
+  const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
+  auto x = static_cast<const uint16_t*>(a.X);
+  const int col_blocks = (a.N + kCols - 1) / kCols;
+  const int full_blocks = (a.ldx % 8 == 0) ? a.N / kCols : 0;  // column blocks eligible for vector loads
+#define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF)                                                                  \
+  spmm_rows16_prepared_kernel<DT, NW, MODE, KB><<<dim3(a.s.M / kRows, GRID_Y), NW * 64, 0, stream>>>(            \
+      base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),                               \
+      reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset, X_PTR, a.ldx,              \
+      a.out_f32 ? static_cast<void*>(static_cast<float*>(a.Y) + (Y_OFF))                                         \
+                : static_cast<void*>(static_cast<uint16_t*>(a.Y) + (Y_OFF)),                                     \
+      a.ldy, a.s.V, L.RB, L.S, a.N - (Y_OFF), a.relu, a.out_f32)
+  if (a.N == 1) {
+    HINM_ROWS16(2, 1, x, 0);
+    return;
+  }
+  if (full_blocks > 0) HINM_ROWS16(1, full_blocks, x, 0);
+  if (col_blocks > full_blocks) {
+    const int off = full_blocks * kCols;  // ragged remainder: shift the column origin
+    HINM_ROWS16(0, col_blocks - full_blocks, x + off, off);
+  }
+#undef HINM_ROWS16
+}
+
+template <int DT>
+void launch_waves(const PreparedArgs& a, hipStream_t stream) {
+  const PreparedLayout L = prepared_layout(a.s);
+  // one batch per wave where possible (every load of the wave in flight at once): waves x batch >= steps
+  if (L.S <= 4) launch_modes<DT, 1, 4>(a, L, stream);
+  else if (L.S <= 16) launch_modes<DT, 4, 4>(a, L, stream);
+  else if (L.S <= 32) launch_modes<DT, 8, 4>(a, L, stream);
+  else if (L.S <= 64) launch_modes<DT, 16, 4>(a, L, stream);
+  else launch_modes<DT, 16, 6>(a, L, stream);
+}
+
+}  // namespace
+
+hipError_t launch_spmm_rows16_prepared(const PreparedArgs& a, hipStream_t stream) {
+  if (a.s.dtype == HINM_F16) launch_waves<HINM_F16>(a, stream);
+  else launch_waves<HINM_BF16>(a, stream);
+  return hipGetLastError();
+}
+
+}  // namespace hinm

@@ -155,7 +155,18 @@ def test_prepared_panel_kernel_edges():
     (64, 4220, 32, 2112, 1),      # K % 8 != 0: same shape class without staging
 ])
 def test_prepared_few_columns(M, K, V, Kv, N, dtype):
-    _check(synth.small_case(M, K, V, Kv, N, dtype, 83), N, [0])
+    # 0 = by shape, 11 = 16-row workgroups (16x16x64 form), 12 = 32-row workgroups (32x32x32 form)
+    _check(synth.small_case(M, K, V, Kv, N, dtype, 83), N, [0, 11, 12])
+
+
+@pytest.mark.parametrize("M,K,V,Kv,N,dtype", [
+    (128, 320, 64, 160, 300, "f16"),      # many column blocks, ragged tail, padded kept columns
+    (192, 256, 96, 64, 40, "bf16"),       # a single step; 96-row tiles: three 32-row blocks
+    (256, 8192, 128, 4416, 16, "bf16"),   # 69 steps: sixteen waves with more than one batch
+])
+def test_prepared_sixteen_row_kernel_beyond_few_columns(M, K, V, Kv, N, dtype):
+    _check(synth.small_case(M, K, V, Kv, N, dtype, 88), N, [11])
+    _check(synth.small_case(M, K, V, Kv, N, dtype, 89), N, [11], relu=True, identity=True)
 
 
 def test_prepared_few_columns_repeatable_and_needs_no_workspace():
