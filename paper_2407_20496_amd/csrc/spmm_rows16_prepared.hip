@@ -23,6 +23,8 @@ constexpr int kStep = 64;   // kept columns per MFMA
 // private LDS slab of one wave: 64 rows x 16 columns, 8-row blocks padded so that the four lane
 // groups of a transposing read fall on different banks
 constexpr int kSlabBytes = 8 * 384;
+constexpr int kXPieces = 4;                 // XMODE 3: 16-byte pieces of the input vector per thread
+constexpr int kXLdsMaxBytes = 48 * 1024;
 
 __device__ __forceinline__ int slab_row_offset(int row) { return row * 32 + (row >> 3) * 128; }
 
@@ -50,22 +52,26 @@ __device__ __forceinline__ u32x8 read_b_operand(const uint8_t* slab, int i, int 
 }
 
 // XMODE: 0 = any N / ld (element loads, slow), 1 = the 16 columns are inside N and rows are
-// 16-byte aligned, 2 = N == 1.  KB = steps whose loads are issued together.
-template <int DT, int NW, int XMODE, int KB>
+// 16-byte aligned, 2 = N == 1, 3 = N == 1 with the input vector staged in LDS (a 64-lane gather of 2-byte
+// elements from global memory costs the address unit one cycle per lane; the vector is small, so the
+// workgroup copies it whole, requested before everything else, and picks from LDS).  KB = steps whose loads
+// are issued together.  RBW = 1: the workgroup owns
+// 16 rows; RBW = 2: both halves of a 32-row block, which share the gathered input rows.
+template <int DT, int NW, int XMODE, int KB, int RBW>
 __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
     const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
-    int V, int RB, int S64, int N, bool relu, bool out_f32) {
-  constexpr int RBW = 1;
+    int V, int RB, int S64, int N, int K, bool relu, bool out_f32) {
   __shared__ __attribute__((aligned(16))) uint8_t slab_all[NW * kSlabBytes];
+  extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];  // XMODE 3: K elements + 8 zeros
   static_assert(RBW * kRows * kCols * 4 <= kSlabBytes, "partial tiles must fit the slab");
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int row0 = blockIdx.x * kRows;  // first row of the layer handled here
+  const int row0 = blockIdx.x * (kRows * RBW);  // first row of the layer handled here
   const int t = row0 / V;
   const int rb32 = (row0 % V) / 32;     // 32-row block of the prepared form that holds these rows
-  const int hf = (row0 % 32) / 16;      // ... and which half of it
+  const int hf = (row0 % 32) / 16;      // ... and which half of it (0 when the workgroup owns both)
   const int n0 = blockIdx.y * kCols;
   const int per_wave = (S64 + NW - 1) / NW;
   const int s_begin = wave * per_wave;
@@ -95,6 +101,30 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
 #pragma unroll
   for (int rb = 0; rb < RBW; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // XMODE 3: this thread's 16-byte pieces of the input vector (requested now, written to LDS after the first
+  // batch of weight loads has been issued); every wave passes the barrier exactly once
+  u32x4 x_mine[kXPieces];
+  bool x_staged = XMODE != 3;
+  if constexpr (XMODE == 3) {
+#pragma unroll
+    for (int r = 0; r < kXPieces; ++r) {
+      const int piece = min((int)threadIdx.x + r * NW * 64, K / 8 - 1);  // beyond the vector: its last piece again
+      x_mine[r] = reinterpret_cast<const u32x4*>(X)[piece];
+    }
+  }
+  auto stage_x = [&]() {
+    if constexpr (XMODE == 3) {
+#pragma unroll
+      for (int r = 0; r < kXPieces; ++r) {
+        const int piece = (int)threadIdx.x + r * NW * 64;
+        if (piece < K / 8) reinterpret_cast<u32x4*>(x_lds)[piece] = x_mine[r];
+      }
+      if (threadIdx.x < 8) x_lds[K + threadIdx.x] = 0;  // where padded kept columns read
+      __syncthreads();
+    }
+    x_staged = true;
+  };
+
   for (int sb = s_begin; sb < s_end; sb += KB) {
     u32x4 a_reg[KB][RBW];
     int idx_reg[KB][RBW];
@@ -112,16 +142,23 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
       const size_t off = (size_t)min(sb + u, s_end - 1) * step_stride;
-      a_reg[u][0] = *reinterpret_cast<const u32x4*>(a_lane + off);
-      const uint32_t word = *reinterpret_cast<const uint32_t*>(idx_lane + off);
-      idx_reg[u][0] = (int)((q >> 1) ? (word >> 16) : (word & 0xFFFFu));
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {  // the second half sits 16 lanes further in the block
+        a_reg[u][rb] = *reinterpret_cast<const u32x4*>(a_lane + off + rb * 256);
+        const uint32_t word = *reinterpret_cast<const uint32_t*>(idx_lane + off + rb * 64);
+        idx_reg[u][rb] = (int)((q >> 1) ? (word >> 16) : (word & 0xFFFFu));
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (!x_staged) stage_x();
     // phase 3: input rows, 16 columns wide
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
       const uint16_t* xr = (col[u] >= 0) ? X + (size_t)col[u] * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
-      if constexpr (XMODE == 1) {
+      if constexpr (XMODE == 3) {
+        b_lo[u] = u32x4{(uint32_t)x_lds[col[u] >= 0 ? col[u] : K], 0, 0, 0};
+        b_hi[u] = u32x4{0, 0, 0, 0};
+      } else if constexpr (XMODE == 1) {
         b_lo[u] = *reinterpret_cast<const u32x4*>(xr);
         b_hi[u] = *reinterpret_cast<const u32x4*>(xr + 8);
       } else if constexpr (XMODE == 2) {
@@ -155,6 +192,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     }
   }
 
+  if (!x_staged) stage_x();  // a wave without steps still owes the barrier
+
   // ---- fixed-order reduction over the waves, epilogue ---------------------------------------
   // D layout: lane holds column lane % 16, rows 4 * (lane / 16) + reg.
   // (the slab is free now; its first kilobytes take this wave's partial tiles)
@@ -182,47 +221,74 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   }
 }
 
-template <int DT, int NW, int KB>
+template <int DT, int NW, int KB, int RBW>
 void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t stream) {
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   auto x = static_cast<const uint16_t*>(a.X);
   const int col_blocks = (a.N + kCols - 1) / kCols;
   const int full_blocks = (a.ldx % 8 == 0) ? a.N / kCols : 0;  // column blocks eligible for vector loads
-#define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF)                                                                  \
-  spmm_rows16_prepared_kernel<DT, NW, MODE, KB><<<dim3(a.s.M / kRows, GRID_Y), NW * 64, 0, stream>>>(            \
-      base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),                               \
-      reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset, X_PTR, a.ldx,              \
-      a.out_f32 ? static_cast<void*>(static_cast<float*>(a.Y) + (Y_OFF))                                         \
-                : static_cast<void*>(static_cast<uint16_t*>(a.Y) + (Y_OFF)),                                     \
-      a.ldy, a.s.V, L.RB, L.S, a.N - (Y_OFF), a.relu, a.out_f32)
+#define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF, LDS)                                                             \
+  spmm_rows16_prepared_kernel<DT, NW, MODE, KB, RBW>                                                             \
+      <<<dim3(a.s.M / (kRows * RBW), GRID_Y), NW * 64, LDS, stream>>>(                                           \
+          base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),                           \
+          reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset, X_PTR, a.ldx,          \
+          a.out_f32 ? static_cast<void*>(static_cast<float*>(a.Y) + (Y_OFF))                                     \
+                    : static_cast<void*>(static_cast<uint16_t*>(a.Y) + (Y_OFF)),                                 \
+          a.ldy, a.s.V, L.RB, L.S, a.N - (Y_OFF), a.s.K, a.relu, a.out_f32)
   if (a.N == 1) {
-    HINM_ROWS16(2, 1, x, 0);
+    // staging the input vector pays once a wave gathers for more than four steps (4096 x 11008 at 50 %:
+    // 10.4 -> 9.9 us; with four steps per wave and 688 workgroups it costs 0.8 us instead)
+    const size_t x_bytes = ((size_t)a.s.K + 8) * 2;
+    const bool stage = a.ldx == 1 && a.s.K % 8 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15u) == 0 &&
+                       a.s.K <= 8 * kXPieces * NW * 64 && x_bytes <= (size_t)kXLdsMaxBytes && L.S > 4 * NW;
+    if (stage) {
+      // slabs (static) plus the vector (dynamic) can exceed the default 64 KB of a workgroup
+      static bool attr_set = false;  // idempotent; a race only repeats it
+      if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(spmm_rows16_prepared_kernel<DT, NW, 3, KB, RBW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kXLdsMaxBytes) != hipSuccess)
+          return;  // the error stays pending and is reported by the caller's hipGetLastError
+        attr_set = true;
+      }
+      HINM_ROWS16(3, 1, x, 0, x_bytes);
+    } else {
+      HINM_ROWS16(2, 1, x, 0, 0);
+    }
     return;
   }
-  if (full_blocks > 0) HINM_ROWS16(1, full_blocks, x, 0);
+  if (full_blocks > 0) HINM_ROWS16(1, full_blocks, x, 0, 0);
   if (col_blocks > full_blocks) {
     const int off = full_blocks * kCols;  // ragged remainder: shift the column origin
-    HINM_ROWS16(0, col_blocks - full_blocks, x + off, off);
+    HINM_ROWS16(0, col_blocks - full_blocks, x + off, off, 0);
   }
 #undef HINM_ROWS16
 }
 
-template <int DT>
+template <int DT, int RBW>
 void launch_waves(const PreparedArgs& a, hipStream_t stream) {
   const PreparedLayout L = prepared_layout(a.s);
   // one batch per wave where possible (every load of the wave in flight at once): waves x batch >= steps
-  if (L.S <= 4) launch_modes<DT, 1, 4>(a, L, stream);
-  else if (L.S <= 16) launch_modes<DT, 4, 4>(a, L, stream);
-  else if (L.S <= 32) launch_modes<DT, 8, 4>(a, L, stream);
-  else if (L.S <= 64) launch_modes<DT, 16, 4>(a, L, stream);
-  else launch_modes<DT, 16, 6>(a, L, stream);
+  if (L.S <= 4) launch_modes<DT, 1, 4, RBW>(a, L, stream);
+  else if (L.S <= 16) launch_modes<DT, 4, 4, RBW>(a, L, stream);
+  else if (L.S <= 32) launch_modes<DT, 8, 4, RBW>(a, L, stream);
+  else if (L.S <= 64) launch_modes<DT, 16, 4, RBW>(a, L, stream);
+  else launch_modes<DT, 16, 6, RBW>(a, L, stream);
+}
+
+template <int DT>
+void launch_dt(const PreparedArgs& a, hipStream_t stream) {
+  // Both halves of a 32-row block in one workgroup share the gathered input rows: worth it when those rows
+  // are wide enough to matter and the grid still covers the chip in one round.
+  const bool both = a.N > 4 && a.s.M / 32 >= 256;
+  if (both) launch_waves<DT, 2>(a, stream);
+  else launch_waves<DT, 1>(a, stream);
 }
 
 }  // namespace
 
 hipError_t launch_spmm_rows16_prepared(const PreparedArgs& a, hipStream_t stream) {
-  if (a.s.dtype == HINM_F16) launch_waves<HINM_F16>(a, stream);
-  else launch_waves<HINM_BF16>(a, stream);
+  if (a.s.dtype == HINM_F16) launch_dt<HINM_F16>(a, stream);
+  else launch_dt<HINM_BF16>(a, stream);
   return hipGetLastError();
 }
 

@@ -153,6 +153,7 @@ def test_prepared_panel_kernel_edges():
     (128, 512, 128, 64, 8),       # a single step: no split
     (64, 4224, 32, 2200, 1),      # one column, more than 32 steps: the input vector is staged in LDS; padded steps
     (64, 4220, 32, 2112, 1),      # K % 8 != 0: same shape class without staging
+    (32, 12288, 32, 8192, 1),     # 128 steps over 16 waves: the 16-row kernel stages the input vector as well
 ])
 def test_prepared_few_columns(M, K, V, Kv, N, dtype):
     # 0 = by shape, 11 = 16-row workgroups (16x16x64 form), 12 = 32-row workgroups (32x32x32 form)
@@ -163,6 +164,7 @@ def test_prepared_few_columns(M, K, V, Kv, N, dtype):
     (128, 320, 64, 160, 300, "f16"),      # many column blocks, ragged tail, padded kept columns
     (192, 256, 96, 64, 40, "bf16"),       # a single step; 96-row tiles: three 32-row blocks
     (256, 8192, 128, 4416, 16, "bf16"),   # 69 steps: sixteen waves with more than one batch
+    (8192, 256, 64, 128, 13, "f16"),      # 256 row blocks of 32: both halves of a block in one workgroup
 ])
 def test_prepared_sixteen_row_kernel_beyond_few_columns(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 88), N, [11])
