@@ -81,6 +81,8 @@ def main():
                     help="also run a plain 256 MiB device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--kernel-us", type=float, default=None,
                     help="icp / ocp workloads: average duration of the cost kernel from a rocprofv3 summary, to price it")
+    ap.add_argument("--ld-pad", type=int, default=0,
+                    help="add this many elements (a multiple of 8) to the leading dimensions of X and Y")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step from the host instead of replaying one captured HIP graph of K steps")
     args = ap.parse_args()
@@ -145,7 +147,7 @@ def main():
         packed.append((W if (l == 0 and not args.no_dense) else None, vals, nm, vec, pin, pout, prep))
         if not (l == 0 and not args.no_dense):
             del W
-    ldn = N if N == 1 else (N + 7) // 8 * 8
+    ldn = N if N == 1 else (N + 7) // 8 * 8 + args.ld_pad
     Xh = np.zeros((c.K, ldn), dtype=np.uint16)
     Xh[:, :N] = c.activations()
     X0 = dev_bits(Xh)

@@ -4,9 +4,29 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "hinm.h"
 
 namespace hinm {
+
+// ---- host: dynamic LDS beyond the default 64 KB of a workgroup -----------------------------------
+
+// Raises the dynamic-LDS limit of one kernel to `bytes`, once per device: the attribute belongs to
+// the device's copy of the code object, so a process that drives several GPUs needs it on each.
+// One flag word per kernel (the template argument is the kernel itself, not its type); setting the
+// attribute twice is harmless, so a race between two first calls only repeats it.
+template <auto Kernel>
+inline hipError_t raise_lds_limit(int bytes) {
+  static std::atomic<uint64_t> done{0};  // bit d: set on device d (devices >= 64 set it on every call)
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 64 && ((done.load(std::memory_order_relaxed) >> dev) & 1u)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev < 64) done.fetch_or(uint64_t{1} << dev, std::memory_order_relaxed);
+  return e;
+}
 
 // ---- 16-bit storage helpers (device) ---------------------------------------------------------
 

@@ -337,10 +337,8 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 hipError_t launch_assignment(const double* cost, int32_t* assign, int problems, int n, hipStream_t stream) {
   if (n <= kSmallP) {  // the cost matrix in LDS: up to 128 KB beside the solver's own arrays
-    auto kernel = icp_assign_kernel<kSmallP, 128, true>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kSmallP * kSmallP * (int)sizeof(double));
-    if (e != hipSuccess) return e;
+    constexpr auto kernel = icp_assign_kernel<kSmallP, 128, true>;
+    if (hipError_t e = raise_lds_limit<kernel>(kSmallP * kSmallP * (int)sizeof(double)); e != hipSuccess) return e;
     kernel<<<problems, 128, (size_t)n * n * sizeof(double), stream>>>(cost, assign, n);
   } else {
     icp_assign_kernel<kMaxP, kThreads, false><<<problems, kThreads, 0, stream>>>(cost, assign, n);

@@ -401,7 +401,9 @@ __global__ __launch_bounds__(kEmitRowThreads<SCORED>) void emit_rows_kernel(cons
   float* score_row = reinterpret_cast<float*>(emit_lds);                     // K floats, only when SCORED
   uint16_t* row = reinterpret_cast<uint16_t*>(emit_lds + (SCORED ? (size_t)K8 * 4 : 0));  // K elements
   constexpr int THREADS = kEmitRowThreads<SCORED>;
-  const int r = blockIdx.x;
+  // Rows are taken last to first: the score pass has just read the layer first to last, so its tail
+  // is the part that the memory-side cache still holds.
+  const int r = (int)gridDim.x - 1 - (int)blockIdx.x;
   const int t = r / V;
   stage_row<THREADS>(row, W + (size_t)r * K, K, vec8);
   if constexpr (SCORED) {
@@ -427,7 +429,7 @@ __global__ __launch_bounds__(kEmitThreads) void gather_rows_kernel(const uint16_
                                                                    bool vec8) {
   extern __shared__ __attribute__((aligned(16))) uint8_t emit_lds[];
   uint16_t* row = reinterpret_cast<uint16_t*>(emit_lds);
-  const int r = blockIdx.x;
+  const int r = (int)gridDim.x - 1 - (int)blockIdx.x;  // last to first, as in emit_rows_kernel
   stage_row<kEmitThreads>(row, W + (size_t)r * K, K, vec8);
   __syncthreads();
   const int32_t* vt = vec_idx + (size_t)(r / V) * Kv;
@@ -490,13 +492,6 @@ __global__ __launch_bounds__(kOrderThreads) void order_kernel(const int32_t* __r
 
 }  // namespace
 
-template <typename Kernel>
-hipError_t allow_lds(Kernel kernel, size_t bytes) {
-  if (bytes <= 64 * 1024) return hipSuccess;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)bytes);
-}
-
 hipError_t launch_pack(const PackArgs& a, hipStream_t stream) {
   const hinm_shape& s = a.s;
   const int T = s.M / s.V;
@@ -546,7 +541,8 @@ hipError_t launch_pack(const PackArgs& a, hipStream_t stream) {
   } else if (a.rho) {
     if (long_rows && s.K <= kEmitRowScoredMaxK) {
       const size_t lds_bytes = 3 * row_bytes;
-      e = allow_lds(emit_rows_kernel<true>, lds_bytes);
+      // a row of W and its float32 saliencies: up to 96 KB, beyond a workgroup's default 64 KB
+      e = raise_lds_limit<emit_rows_kernel<true>>(3 * kEmitRowScoredMaxK * 2);
       if (e != hipSuccess) return e;
       emit_rows_kernel<true><<<(unsigned)s.M, kEmitRowThreads<true>, lds_bytes, stream>>>(Wb, a.rho, a.vec_idx, vals, a.nm_idx,
                                                                                  s.K, s.V, s.Kv, vec8, rho_vec4);

@@ -247,14 +247,8 @@ inline size_t panel_lds_bytes(int K, int waves) {
 template <int DT, int RB, int WAVES>
 hipError_t launch_waves(const PreparedArgs& a, int n_blocks, int tile_groups, hipStream_t stream) {
   const PreparedLayout L = prepared_layout(a.s);
-  auto kernel = spmm_panel_prepared_kernel<DT, RB, WAVES>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kernel = spmm_panel_prepared_kernel<DT, RB, WAVES>;
+  if (hipError_t e = raise_lds_limit<kernel>(160 * 1024); e != hipSuccess) return e;
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   const int nb8 = (n_blocks + 7) / 8 * 8;  // ids are laid out in groups of 8 column blocks
   kernel<<<dim3((unsigned)(nb8 * tile_groups)), WAVES * 64, panel_lds_bytes(a.s.K, WAVES), stream>>>(

@@ -243,13 +243,8 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t st
                        a.s.K <= 8 * kXPieces * NW * 64 && x_bytes <= (size_t)kXLdsMaxBytes && L.S > 4 * NW;
     if (stage) {
       // slabs (static) plus the vector (dynamic) can exceed the default 64 KB of a workgroup
-      static bool attr_set = false;  // idempotent; a race only repeats it
-      if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(spmm_rows16_prepared_kernel<DT, NW, 3, KB, RBW>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kXLdsMaxBytes) != hipSuccess)
-          return;  // the error stays pending and is reported by the caller's hipGetLastError
-        attr_set = true;
-      }
+      if (raise_lds_limit<spmm_rows16_prepared_kernel<DT, NW, 3, KB, RBW>>(kXLdsMaxBytes) != hipSuccess)
+        return;  // the error stays pending and is reported by the caller's hipGetLastError
       HINM_ROWS16(3, 1, x, 0, x_bytes);
     } else {
       HINM_ROWS16(2, 1, x, 0, 0);

@@ -224,14 +224,9 @@ __global__ __launch_bounds__(NWV * 64, (min_waves_per_simd<NWV, KB, NG, RBW, XS>
 template <int DT, int NWV, int KB, int NG, int RBW, bool XS>
 void launch_kernel(const PreparedArgs& a, const PreparedLayout& L, size_t lds_bytes, hipStream_t stream) {
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
-  auto kernel = spmm_skinny_prepared_kernel<DT, NWV, KB, NG, RBW, XS>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)(NWV * kSlabBytes + kXLdsMaxBytes)) != hipSuccess)
-      return;  // the error stays pending and is reported by the caller's hipGetLastError
-    attr_set = true;
-  }
+  constexpr auto kernel = spmm_skinny_prepared_kernel<DT, NWV, KB, NG, RBW, XS>;
+  if (raise_lds_limit<kernel>((int)(NWV * kSlabBytes + kXLdsMaxBytes)) != hipSuccess)
+    return;  // the error stays pending and is reported by the caller's hipGetLastError
   kernel<<<dim3(L.RB / RBW, L.T), NWV * 64, lds_bytes, stream>>>(
       base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),
       reinterpret_cast<const int32_t*>(base + L.pi_out_offset), static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy,

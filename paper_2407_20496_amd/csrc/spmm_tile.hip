@@ -553,14 +553,8 @@ hipError_t launch_one(const SpmmArgs& a, hipStream_t stream) {
   const int64_t work = (int64_t)n_blocks * T;
   const int work_per_xcd = (int)((work + 7) / 8);
   const size_t lds_bytes = L::total_bytes(V);
-  auto kernel = spmm_tile_kernel<DT, RB, KSUB>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kernel = spmm_tile_kernel<DT, RB, KSUB>;
+  if (hipError_t e = raise_lds_limit<kernel>((int)lds_bytes); e != hipSuccess) return e;
   kernel<<<dim3((unsigned)(work_per_xcd * 8)), kThreads, lds_bytes, stream>>>(
       static_cast<const uint16_t*>(a.vals), a.nm_idx, a.vec_idx, a.pi_in, a.pi_out,
       static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy, T, a.s.Kv, a.N, n_blocks, work_per_xcd, a.relu,
@@ -575,14 +569,8 @@ hipError_t launch_dma(const SpmmArgs& a, hipStream_t stream) {
   const int n_blocks = (a.N + NB - 1) / NB;
   const int64_t work = (int64_t)n_blocks * T;
   const int work_per_xcd = (int)((work + 7) / 8);
-  auto kernel = spmm_tile_dma_kernel<DT, RB, NB>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kernel = spmm_tile_dma_kernel<DT, RB, NB>;
+  if (hipError_t e = raise_lds_limit<kernel>(C::LDS_BYTES); e != hipSuccess) return e;
   kernel<<<dim3((unsigned)(work_per_xcd * 8)), NB, C::LDS_BYTES, stream>>>(
       static_cast<const uint16_t*>(a.vals), a.nm_idx, a.vec_idx, a.pi_in, a.pi_out, static_cast<const uint16_t*>(a.X),
       a.ldx, a.Y, a.ldy, T, a.s.Kv, a.N, n_blocks, work_per_xcd, a.relu, a.out_f32);

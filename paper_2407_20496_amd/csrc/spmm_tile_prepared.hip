@@ -318,14 +318,8 @@ hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream) {
   const int n_blocks = (a.N + NB - 1) / NB;
   const int64_t work = (int64_t)n_blocks * L.T;
   const int work_per_xcd = (int)((work + 7) / 8);
-  auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST>;
+  if (hipError_t e = raise_lds_limit<kernel>(C::LDS_BYTES); e != hipSuccess) return e;
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   kernel<<<dim3((unsigned)(work_per_xcd * 8)), C::THREADS, C::LDS_BYTES, stream>>>(
       base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),
