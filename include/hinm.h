@@ -83,10 +83,10 @@ enum {
   HINM_KERNEL_SMFMAC = 0x200u,    /* a sparse-MFMA kernel: 32x32 tiles (V in {32,64,96,128}, Kv % 32 == 0,
                                      ld % 8 == 0) or else the 16-column form (V % 16 == 0) */
   HINM_KERNEL_GEMV = 0x400u,      /* 16-column sparse-MFMA form with k split over the waves; N <= 16, V % 16 == 0 */
-  /* hinm_spmm_prepared and hinm_spmm_vectors only, tuning aid: bits 16..19 pin one kernel configuration
+  /* hinm_spmm_prepared and hinm_spmm_vectors only, tuning aid: bits 16..21 pin one kernel configuration
    * (0 = by shape); a configuration that does not fit the shape returns HINM_ERR_UNSUPPORTED */
   HINM_VARIANT_SHIFT = 16,
-  HINM_VARIANT_MASK = 0xF0000u
+  HINM_VARIANT_MASK = 0x3F0000u
 };
 
 typedef struct {

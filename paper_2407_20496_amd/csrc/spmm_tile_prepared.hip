@@ -27,9 +27,10 @@
 namespace hinm {
 namespace {
 
-template <int RB, int NB, int KSUB, int ST>
+template <int RB, int NB, int KSUB, int ST, int WC>
 struct TileCfg {
-  static constexpr int NW = NB / 64;
+  static constexpr int NW = NB / WC;                            // waves; each owns WC of the NB columns
+  static constexpr int CBS = WC / 32;                           // 32-column accumulator blocks per wave
   static constexpr int THREADS = NW * 64;
   static constexpr int KS = 32 * KSUB;
   static constexpr int ROW_BYTES = NB * 2;
@@ -50,17 +51,20 @@ struct TileCfg {
   static constexpr int EPI_BYTES = 32 * RB * Y_STRIDE;
   static constexpr int LDS_BYTES = (STAGES_BYTES > EPI_BYTES) ? STAGES_BYTES : EPI_BYTES;
   static_assert(NB == 256 || NB == 512, "column block");
+  static_assert(WC == 64 || WC == 32, "columns per wave");
   static_assert(KSUB == 1 || KSUB == 2 || KSUB == 4, "half a step, one step or two steps per stage");
-  static_assert(B_PER_WAVE == 4 * KSUB, "copy split");
+  static_assert(B_PER_WAVE * NW * (NB == 512 ? 1 : 2) == KS, "copy split");
+  static_assert(ST == 2 || B_PER_WAVE == 4 * KSUB, "deeper pipelines: the wait table assumes four copies per substep");
   static_assert(ST >= 2 && ST <= 4 && (A_INSTR + NW - 1) / NW <= 3, "wait table covers these");
 };
 
-template <int DT, int RB, int NB, int KSUB, int ST>
-__global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
+template <int DT, int RB, int NB, int KSUB, int ST, int WC>
+__global__ __launch_bounds__(NB / WC * 64) void spmm_tile_prepared_kernel(
     const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
     const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
     int T, int S64, int N, int n_blocks, int work_per_xcd, bool relu, bool out_f32) {
-  using C = TileCfg<RB, NB, KSUB, ST>;
+  using C = TileCfg<RB, NB, KSUB, ST, WC>;
+  constexpr int CBS = C::CBS;
   constexpr int V = 32 * RB;
   constexpr int NW = C::NW;
   constexpr int KS = C::KS;
@@ -167,20 +171,21 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
   const int qh = lane >> 5;   // lane group
   const int i16 = lane & 15;
   const int sw_lane = swizzle_of_row(i16 >> 2);
-  int b_col_off[2];
+  int b_col_off[CBS];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) b_col_off[cb] = (((wave * 4 + cb * 2 + (i32 >> 4)) ^ sw_lane) * 32) + (i16 & 3) * 8;
+  for (int cb = 0; cb < CBS; ++cb)
+    b_col_off[cb] = (((wave * (WC / 16) + cb * 2 + (i32 >> 4)) ^ sw_lane) * 32) + (i16 & 3) * 8;
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_t*)lds;
   // per-lane part of the transposing-read address: row 8 qb + (i16 / 4), swizzled column unit
-  uint32_t b_lane_off[2];
+  uint32_t b_lane_off[CBS];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) b_lane_off[cb] = (8 * qh + (i16 >> 2)) * C::ROW_BYTES + b_col_off[cb];
+  for (int cb = 0; cb < CBS; ++cb) b_lane_off[cb] = (8 * qh + (i16 >> 2)) * C::ROW_BYTES + b_col_off[cb];
 
-  f32x16 acc[RB][2];
+  f32x16 acc[RB][CBS];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CBS; ++cb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[rb][cb][e] = 0.f;
 
@@ -203,7 +208,8 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
     const uint8_t* as = a_buffer(stage_idx);
     const uint32_t stage_addr = lds_base + (uint32_t)(stage - lds);
     u32x8 b0 = read_b(stage_addr, 0, sub_tag);
-    u32x8 b1 = read_b(stage_addr, 1, sub_tag);
+    u32x8 b1 = b0;
+    if constexpr (CBS == 2) b1 = read_b(stage_addr, 1, sub_tag);
     u32x4 a[RB];
     int idx[RB];
 #pragma unroll
@@ -214,15 +220,16 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
       // the index register holds the nibbles of both substeps of a 64-column step
       if (KSUB == 1 && (stage_idx & 1)) idx[rb] = (int)((uint32_t)idx[rb] >> 16);
     }
-    lds_wait_tr(b0, b1);
+    if constexpr (CBS == 2) lds_wait_tr(b0, b1);
+    else lds_wait_tr(b0);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       if constexpr (SUB == 1) {
         acc[rb][0] = smfmac_32x32x32<DT, 1>(a[rb], b0, acc[rb][0], idx[rb]);
-        acc[rb][1] = smfmac_32x32x32<DT, 1>(a[rb], b1, acc[rb][1], idx[rb]);
+        if constexpr (CBS == 2) acc[rb][1] = smfmac_32x32x32<DT, 1>(a[rb], b1, acc[rb][1], idx[rb]);
       } else {
         acc[rb][0] = smfmac_32x32x32<DT, 0>(a[rb], b0, acc[rb][0], idx[rb]);
-        acc[rb][1] = smfmac_32x32x32<DT, 0>(a[rb], b1, acc[rb][1], idx[rb]);
+        if constexpr (CBS == 2) acc[rb][1] = smfmac_32x32x32<DT, 0>(a[rb], b1, acc[rb][1], idx[rb]);
       }
     }
   };
@@ -271,8 +278,8 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
         const int r = t * V + 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
         const int64_t out_row = out_rows[r];
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const int n = n0 + wave * 64 + cb * 32 + i32;
+        for (int cb = 0; cb < CBS; ++cb) {
+          const int n = n0 + wave * WC + cb * 32 + i32;
           float v = acc[rb][cb][e];
           if (relu) v = v > 0.f ? v : 0.f;
           if (n < N) Yf[out_row * ldy + n] = v;
@@ -284,11 +291,11 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CBS; ++cb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
-        const int col = wave * 64 + cb * 32 + i32;
+        const int col = wave * WC + cb * 32 + i32;
         float v = acc[rb][cb][e];
         if (relu) v = v > 0.f ? v : 0.f;
         *reinterpret_cast<uint16_t*>(lds + row * C::Y_STRIDE + col * 2) = float_to_bits<DT>(v);
@@ -311,14 +318,14 @@ __global__ __launch_bounds__(NB) void spmm_tile_prepared_kernel(
   }
 }
 
-template <int DT, int RB, int NB, int KSUB, int ST>
+template <int DT, int RB, int NB, int KSUB, int ST, int WC = 64>
 hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream) {
-  using C = TileCfg<RB, NB, KSUB, ST>;
+  using C = TileCfg<RB, NB, KSUB, ST, WC>;
   const PreparedLayout L = prepared_layout(a.s);
   const int n_blocks = (a.N + NB - 1) / NB;
   const int64_t work = (int64_t)n_blocks * L.T;
   const int work_per_xcd = (int)((work + 7) / 8);
-  constexpr auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST>;
+  constexpr auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST, WC>;
   if (hipError_t e = raise_lds_limit<kernel>(C::LDS_BYTES); e != hipSuccess) return e;
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   kernel<<<dim3((unsigned)(work_per_xcd * 8)), C::THREADS, C::LDS_BYTES, stream>>>(
@@ -328,23 +335,27 @@ hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// By shape: wide column blocks halve the re-reads of the stored values when there are enough of
-// them to fill the chip; short k loops prefer small stages so that several workgroups share a
-// compute unit and cover each other's start-up and epilogue.
+// By shape.  Wide column blocks halve the re-reads of the stored values when there are enough of them
+// to fill the chip.  Waves of 32 columns (twice as many waves per workgroup) hide the latency of a stage's
+// copies better and cost 40 % more LDS reads per MFMA: they win wherever a compute unit holds a single
+// workgroup and the layer is not large enough to be bound by LDS and L2 throughput (measured on the
+// encoder, convolution and MLP shapes: 5 to 20 %; the 16384 x 16384 x 8192 layer is 2 % slower with them).
 inline int choose_variant(const PreparedArgs& a) {
   const PreparedLayout L = prepared_layout(a.s);
   const int64_t wide_blocks = (int64_t)L.T * ((a.N + 511) / 512);
-  if (a.N >= 1024 && wide_blocks >= 256) return 3;  // 512 columns, 64-column stages, 2 deep
-  // 128-row tiles with a short k loop: the wide block still pays with half as many workgroups as units
-  if (a.N >= 1024 && L.RB == 4 && L.S <= 8 && wide_blocks >= 128) return 3;
+  // 512 columns, 64-column stages, 2 deep: sixteen 32-column waves up to a few rounds of workgroups, eight
+  // 64-column waves beyond
+  if (a.N >= 1024 && wide_blocks >= 256) return wide_blocks <= 1024 ? 16 : 3;
   const int64_t blocks = (int64_t)L.T * ((a.N + 255) / 256);
-  // short k loops with several workgroups per compute unit: 32-column stages, 2 deep (the workgroups
-  // cover each other's start-up and epilogue); with fewer workgroups the larger stages below win
-  if (L.S <= 8 && blocks > 512) return 8;
+  // short k loops: 32-column stages, 2 deep, so that several workgroups share a compute unit and cover each
+  // other's start-up and epilogue (128-row tiles with at least half as many wide blocks as units; or many
+  // workgroups per unit)
+  if (a.N >= 1024 && L.RB == 4 && L.S <= 8 && wide_blocks >= 128) return 17;
+  if (L.S <= 8 && blocks > 512) return 17;
   // At most one workgroup per compute unit: every stage then waits one full memory round trip, and
   // 128-column stages halve the number of round trips.
-  if (L.RB <= 2 && L.S % 2 == 0 && blocks <= 256) return 10;
-  return 1;                                         // 256 columns, 64-column stages, 2 deep
+  if (L.RB <= 2 && L.S % 2 == 0 && blocks <= 256) return 13;
+  return 14;                                        // 256 columns, 64-column stages, 2 deep
 }
 
 template <int DT, int RB>
@@ -364,6 +375,14 @@ hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
         if (prepared_layout(a.s).S % 2 == 0) return launch_cfg<DT, RB, 256, 4, 2>(a, stream);
       }
       break;
+    case 13:  // as 10, eight waves of 32 columns each
+      if constexpr (RB <= 2) {
+        if (prepared_layout(a.s).S % 2 == 0) return launch_cfg<DT, RB, 256, 4, 2, 32>(a, stream);
+      }
+      break;
+    case 14: return launch_cfg<DT, RB, 256, 2, 2, 32>(a, stream);  // as 1, eight waves of 32 columns each
+    case 16: return launch_cfg<DT, RB, 512, 2, 2, 32>(a, stream);  // as 3, sixteen waves of 32 columns each
+    case 17: return launch_cfg<DT, RB, 256, 1, 2, 32>(a, stream);  // as 8, eight waves of 32 columns each
     default: break;
   }
   return launch_cfg<DT, RB, 256, 2, 3>(a, stream);
