@@ -238,7 +238,7 @@ hinm_status hinm_spmm(const hinm_shape* shape, int32_t N,
  * rounding, pi_in / pi_out, ldx / ldy and alignment rules as for hinm_spmm.  flags: HINM_EPI_RELU,
  * HINM_OUT_F32, HINM_KERNEL_REFERENCE (one thread per output element), the variant bits (1 =
  * register-staged tile kernel, 2 / 3 = direct-to-LDS tile kernel with 256- / 512-column blocks,
- * which need Kv % 64 == 0); anything else returns HINM_ERR_UNSUPPORTED.  V in {32, 64, 96, 128}
+ * 4 / 5 = the same with twice as many waves of half the width; 2..5 need Kv % 64 == 0); anything else returns HINM_ERR_UNSUPPORTED.  V in {32, 64, 96, 128}
  * with N > 1 runs on the dense MFMA, other shapes on the plain kernel.  Needs no workspace. */
 hinm_status hinm_spmm_vectors(const hinm_shape* shape, int32_t N,
                               const void* vals_v, const int32_t* vec_idx,

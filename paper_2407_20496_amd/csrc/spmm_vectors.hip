@@ -274,10 +274,12 @@ __global__ __launch_bounds__(kThreads) void spmm_vectors_kernel(
 //       fragment reads of 16 consecutive rows cover all banks once.
 // One barrier per stage; a stage is multiplied while the copies of the next one are in flight.
 // ---------------------------------------------------------------------------------------------
-template <int RB, int NB>
+template <int RB, int NB, int WC>
 struct DmaCfg {
   static constexpr int V = 32 * RB;
-  static constexpr int NW = NB / 64;
+  static constexpr int NW = NB / WC;                          // waves; each owns WC of the NB columns
+  static constexpr int THREADS = NW * 64;
+  static constexpr int CBS = WC / 32;                         // 32-column accumulator blocks per wave
   static constexpr int ROW_BYTES = NB * 2;
   static constexpr int B_BYTES = 64 * ROW_BYTES;
   static constexpr int A_BYTES = V * 128;
@@ -290,17 +292,19 @@ struct DmaCfg {
   static constexpr int EPI_BYTES = V * Y_STRIDE;
   static constexpr int LDS_BYTES = (2 * STAGE_BYTES > EPI_BYTES) ? 2 * STAGE_BYTES : EPI_BYTES;
   static_assert(NB == 256 || NB == 512, "column block");
+  static_assert(WC == 64 || WC == 32, "columns per wave");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS of a compute unit");
 };
 
-template <int DT, int RB, int NB>
-__global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
+template <int DT, int RB, int NB, int WC>
+__global__ __launch_bounds__(NB / WC * 64) void spmm_vectors_dma_kernel(
     const uint16_t* __restrict__ vals_v, const int32_t* __restrict__ vec_idx, const int32_t* __restrict__ pi_in,
     const int32_t* __restrict__ pi_out, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y,
     int64_t ldy, int T, int Kv, int N, int n_blocks, int work_per_xcd, bool relu, bool out_f32) {
-  using C = DmaCfg<RB, NB>;
+  using C = DmaCfg<RB, NB, WC>;
   constexpr int V = C::V;
   constexpr int NW = C::NW;
+  constexpr int CBS = C::CBS;
   constexpr int RPW = C::ROWS_PER_WAVE;
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
@@ -385,21 +389,21 @@ __global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
   const int i16 = lane & 15;
   const int sw_lane = swizzle_of_row(i16 >> 2);
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_t*)lds;
-  uint32_t b_lane_off[2];
+  uint32_t b_lane_off[CBS];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb)
-    b_lane_off[cb] = (8 * qh + (i16 >> 2)) * C::ROW_BYTES + (((wave * 4 + cb * 2 + (i32 >> 4)) ^ sw_lane) * 32) +
-                     (i16 & 3) * 8;
+  for (int cb = 0; cb < CBS; ++cb)
+    b_lane_off[cb] = (8 * qh + (i16 >> 2)) * C::ROW_BYTES +
+                     (((wave * (WC / 16) + cb * 2 + (i32 >> 4)) ^ sw_lane) * 32) + (i16 & 3) * 8;
   // A fragment of the 16-column substep q: chunk 2 q + qh of row i32 (+ 32 rb), at its swizzled place
   uint32_t a_lane_off[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) a_lane_off[q] = i32 * 128 + (((2 * q + qh) ^ ((i32 >> 1) & 7)) * 16);
 
-  f32x16 acc[RB][2];
+  f32x16 acc[RB][CBS];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CBS; ++cb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[rb][cb][e] = 0.f;
 
@@ -411,9 +415,9 @@ __global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
     const uint8_t* as = a_buffer(stage_idx);
     constexpr int R0 = (Q0 * 16 + 0) * C::ROW_BYTES, R1 = (Q0 * 16 + 4) * C::ROW_BYTES,
                   R2 = (Q0 * 16 + 16) * C::ROW_BYTES, R3 = (Q0 * 16 + 20) * C::ROW_BYTES;
-    u32x2 r[2][4];
+    u32x2 r[CBS][4];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CBS; ++cb)
       lds_read_tr16_x4<R0, R1, R2, R3>(stage_addr + b_lane_off[cb], r[cb][0], r[cb][1], r[cb][2], r[cb][3]);
     u32x4 a[2][RB];
 #pragma unroll
@@ -422,8 +426,14 @@ __global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
       for (int rb = 0; rb < RB; ++rb)
         a[h][rb] = *reinterpret_cast<const u32x4*>(as + rb * 4096 + a_lane_off[Q0 + h]);
     u32x8 b0 = u32x8{r[0][0].x, r[0][0].y, r[0][1].x, r[0][1].y, r[0][2].x, r[0][2].y, r[0][3].x, r[0][3].y};
-    u32x8 b1 = u32x8{r[1][0].x, r[1][0].y, r[1][1].x, r[1][1].y, r[1][2].x, r[1][2].y, r[1][3].x, r[1][3].y};
-    lds_wait_tr(b0, b1);
+    u32x8 b1 = b0;
+    if constexpr (CBS == 2) {
+      b1 = u32x8{r[CBS - 1][0].x, r[CBS - 1][0].y, r[CBS - 1][1].x, r[CBS - 1][1].y,
+                 r[CBS - 1][2].x, r[CBS - 1][2].y, r[CBS - 1][3].x, r[CBS - 1][3].y};
+      lds_wait_tr(b0, b1);
+    } else {
+      lds_wait_tr(b0);
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const u32x4 bf0 = u32x4{b0[4 * h], b0[4 * h + 1], b0[4 * h + 2], b0[4 * h + 3]};
@@ -431,7 +441,7 @@ __global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         acc[rb][0] = mfma_32x32x16<DT>(a[h][rb], bf0, acc[rb][0]);
-        acc[rb][1] = mfma_32x32x16<DT>(a[h][rb], bf1, acc[rb][1]);
+        if constexpr (CBS == 2) acc[rb][1] = mfma_32x32x16<DT>(a[h][rb], bf1, acc[rb][1]);
       }
     }
   };
@@ -460,8 +470,8 @@ __global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
         const int r = t * V + 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
         const int64_t out_row = pi_out ? pi_out[r] : r;
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const int n = n0 + wave * 64 + cb * 32 + i32;
+        for (int cb = 0; cb < CBS; ++cb) {
+          const int n = n0 + wave * WC + cb * 32 + i32;
           float v = acc[rb][cb][e];
           if (relu) v = v > 0.f ? v : 0.f;
           if (n < N) Yf[out_row * ldy + n] = v;
@@ -473,11 +483,11 @@ __global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CBS; ++cb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
-        const int col = wave * 64 + cb * 32 + i32;
+        const int col = wave * WC + cb * 32 + i32;
         float v = acc[rb][cb][e];
         if (relu) v = v > 0.f ? v : 0.f;
         *reinterpret_cast<uint16_t*>(lds + row * C::Y_STRIDE + col * 2) = float_to_bits<DT>(v);
@@ -486,7 +496,7 @@ __global__ __launch_bounds__(NB) void spmm_vectors_dma_kernel(
   uint16_t* Yh = static_cast<uint16_t*>(Y);
   constexpr int LANES_PER_ROW = NB / 8;
   const int chunk = tid % LANES_PER_ROW;
-  for (int row = tid / LANES_PER_ROW; row < V; row += NB / LANES_PER_ROW) {
+  for (int row = tid / LANES_PER_ROW; row < V; row += C::THREADS / LANES_PER_ROW) {
     const int r = t * V + row;
     const int64_t out_row = pi_out ? pi_out[r] : r;
     const int n = n0 + chunk * 8;
@@ -540,16 +550,16 @@ hipError_t launch_one(const VectorsArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int DT, int RB, int NB>
+template <int DT, int RB, int NB, int WC>
 hipError_t launch_dma(const VectorsArgs& a, hipStream_t stream) {
-  using C = DmaCfg<RB, NB>;
+  using C = DmaCfg<RB, NB, WC>;
   const int T = a.s.M / C::V;
   const int n_blocks = (a.N + NB - 1) / NB;
   const int64_t work = (int64_t)n_blocks * T;
   const int work_per_xcd = (int)((work + 7) / 8);
-  constexpr auto kernel = spmm_vectors_dma_kernel<DT, RB, NB>;
+  constexpr auto kernel = spmm_vectors_dma_kernel<DT, RB, NB, WC>;
   if (hipError_t e = raise_lds_limit<kernel>(C::LDS_BYTES); e != hipSuccess) return e;
-  kernel<<<dim3((unsigned)(work_per_xcd * 8)), NB, C::LDS_BYTES, stream>>>(
+  kernel<<<dim3((unsigned)(work_per_xcd * 8)), C::THREADS, C::LDS_BYTES, stream>>>(
       static_cast<const uint16_t*>(a.vals_v), a.vec_idx, a.pi_in, a.pi_out, static_cast<const uint16_t*>(a.X), a.ldx,
       a.Y, a.ldy, T, a.s.Kv, a.N, n_blocks, work_per_xcd, a.relu, a.out_f32);
   return hipGetLastError();
@@ -558,8 +568,10 @@ hipError_t launch_dma(const VectorsArgs& a, hipStream_t stream) {
 template <int DT, int RB>
 hipError_t launch_rb(const VectorsArgs& a, hipStream_t stream) {
   switch (spmm_vectors_variant(a)) {
-    case 2: return launch_dma<DT, RB, 256>(a, stream);
-    case 3: return launch_dma<DT, RB, 512>(a, stream);
+    case 2: return launch_dma<DT, RB, 256, 64>(a, stream);
+    case 3: return launch_dma<DT, RB, 512, 64>(a, stream);
+    case 4: return launch_dma<DT, RB, 256, 32>(a, stream);
+    case 5: return launch_dma<DT, RB, 512, 32>(a, stream);
     default: return launch_one<DT, RB>(a, stream);
   }
 }
@@ -577,23 +589,27 @@ hipError_t launch_dt(const VectorsArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-// 1 = register-staged kernel, 2 / 3 = direct-to-LDS kernel with 256- / 512-column blocks.
+// 1 = register-staged kernel, 2 / 3 = direct-to-LDS kernel with 256- / 512-column blocks and 64-column waves,
+// 4 / 5 = the same blocks with 32-column waves (twice as many waves per workgroup).
 int spmm_vectors_variant(const VectorsArgs& a) {
   if (a.variant) return a.variant;
   if (a.s.Kv % 64 != 0) return 1;
   // 512-column blocks halve the re-reads of the stored values; they pay when there are enough of them to
   // fill the chip and the k loop is long enough to amortise the larger start-up and epilogue
   const int64_t wide_blocks = (int64_t)(a.s.M / a.s.V) * ((a.N + 511) / 512);
-  if (a.N >= 1024 && wide_blocks >= 256 && a.s.Kv >= 1024) return 3;
-  if (a.N >= 1024 && wide_blocks >= 192 && a.s.V == 128) return 3;  // measured on 3072 x 768, N = 4096: 33.4 -> 25.7 us
-  return 2;
+  // Waves of 32 columns (twice as many per workgroup) cover the latency of a stage's copies better and read
+  // more from LDS per MFMA: 5 to 20 % faster on every shape measured except the largest (16384 x 16384 x 8192).
+  const int wide = wide_blocks <= 1024 ? 5 : 3;
+  if (a.N >= 1024 && wide_blocks >= 256 && a.s.Kv >= 1024) return wide;
+  if (a.N >= 1024 && wide_blocks >= 192 && a.s.V == 128) return wide;  // measured on 3072 x 768, N = 4096: 34.0 -> 23.3 us
+  return 4;
 }
 
 bool spmm_vectors_mfma_supported(const VectorsArgs& a) {
   const int V = a.s.V;
   if (!(V == 32 || V == 64 || V == 96 || V == 128)) return false;
   if (a.ldx % 8 != 0 || a.ldy % 8 != 0) return false;
-  if (a.variant < 0 || a.variant > 3 || (a.variant >= 2 && a.s.Kv % 64 != 0)) return false;
+  if (a.variant < 0 || a.variant > 5 || (a.variant >= 2 && a.s.Kv % 64 != 0)) return false;
   const int64_t work = (int64_t)((a.N + kNB - 1) / kNB) * (a.s.M / V);
   return work < (1ll << 28);
 }

@@ -165,7 +165,7 @@ def test_spmm_vectors_matches_the_oracle(M, K, V, Kv, N, dtype, flags):
         assert np.array_equal(got, orc.round_to_storage(got32, dtype))
     # every tile kernel that fits the shape, pinned through the variant bits
     if V % 32 == 0 and N > 1 and not flags & 0x100:
-        for variant in (1, 2, 3):
+        for variant in (1, 2, 3, 4, 5):
             if variant >= 2 and Kv % 64:
                 continue
             g = gu.gpu_spmm_vectors(pv, Xb, pin, pout, flags=(flags & 1) | 2 | variant << 16)
