@@ -9,7 +9,7 @@ from oracle import hinm_oracle as orc
 pytestmark = pytest.mark.gpu
 
 OUT_F32, RELU = 2, 1
-VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13, 14, 15]   # 13, 14 = 32-column waves; 15 = LDS-resident panel kernel (small K only)
+VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13, 14, 16, 17, 15]   # 13, 14, 16, 17 = 32-column waves; 15 = LDS-resident panel kernel (small K only)
 
 
 def _ulp_bf16(y):
