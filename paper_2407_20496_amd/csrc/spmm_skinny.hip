@@ -131,8 +131,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_skinny_kernel(
     for (int u = 0; u < KB; ++u) {
       const uint16_t* xr = X + (size_t)col[u] * ldx + n0;
       if constexpr (XMODE == 1) {
-        b_lo[u] = *reinterpret_cast<const u32x4*>(xr);
-        b_hi[u] = *reinterpret_cast<const u32x4*>(xr + 8);
+        // Lanes 2 j and 2 j + 1 fetch the two 16-byte halves of one row (rows j and 32 + j of the step):
+        // neighbouring lanes then fall into one cache line, which halves the tag look-ups that a gather of
+        // rows scattered by the input-channel order costs.
+        const int c_lo = __builtin_amdgcn_ds_bpermute((lane >> 1) * 4, col[u]);
+        const int c_hi = __builtin_amdgcn_ds_bpermute((32 + (lane >> 1)) * 4, col[u]);
+        b_lo[u] = *reinterpret_cast<const u32x4*>(X + (size_t)c_lo * ldx + n0 + 8 * (lane & 1));
+        b_hi[u] = *reinterpret_cast<const u32x4*>(X + (size_t)c_hi * ldx + n0 + 8 * (lane & 1));
       } else if constexpr (XMODE == 2) {
         b_lo[u] = u32x4{(uint32_t)xr[0], 0, 0, 0};
         b_hi[u] = u32x4{0, 0, 0, 0};
@@ -149,9 +154,14 @@ __global__ __launch_bounds__(NW * 64) void spmm_skinny_kernel(
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
       const bool live = sb + u < s_end;  // wave-uniform
-      uint8_t* wr = slab + slab_row_offset(lane);
-      *reinterpret_cast<u32x4*>(wr) = b_lo[u];
-      *reinterpret_cast<u32x4*>(wr + 16) = b_hi[u];
+      if constexpr (XMODE == 1) {  // half rows: see the loads
+        *reinterpret_cast<u32x4*>(slab + slab_row_offset(lane >> 1) + 16 * (lane & 1)) = b_lo[u];
+        *reinterpret_cast<u32x4*>(slab + slab_row_offset(32 + (lane >> 1)) + 16 * (lane & 1)) = b_hi[u];
+      } else {
+        uint8_t* wr = slab + slab_row_offset(lane);
+        *reinterpret_cast<u32x4*>(wr) = b_lo[u];
+        *reinterpret_cast<u32x4*>(wr + 16) = b_hi[u];
+      }
       wave_sync_lds();
       u32x8 b = read_b_operand(slab, i, q);
       if (!live) b = u32x8{0, 0, 0, 0, 0, 0, 0, 0};
