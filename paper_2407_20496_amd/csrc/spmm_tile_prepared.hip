@@ -318,20 +318,25 @@ __global__ __launch_bounds__(NB / WC * 64) void spmm_tile_prepared_kernel(
   }
 }
 
+// Launches the tiles [tile_base, tile_base + tile_count) of the layer (tile_count < 0: all of them).  The kernel
+// numbers its tiles from zero: the tables it indexes by tile are handed over already advanced to tile_base.
 template <int DT, int RB, int NB, int KSUB, int ST, int WC = 64>
-hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream) {
+hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream, int tile_base = 0, int tile_count = -1) {
   using C = TileCfg<RB, NB, KSUB, ST, WC>;
   const PreparedLayout L = prepared_layout(a.s);
+  const int T = tile_count < 0 ? L.T : tile_count;
   const int n_blocks = (a.N + NB - 1) / NB;
-  const int64_t work = (int64_t)n_blocks * L.T;
+  const int64_t work = (int64_t)n_blocks * T;
   const int work_per_xcd = (int)((work + 7) / 8);
   constexpr auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST, WC>;
   if (hipError_t e = raise_lds_limit<kernel>(C::LDS_BYTES); e != hipSuccess) return e;
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
+  const size_t tb = (size_t)tile_base;
   kernel<<<dim3((unsigned)(work_per_xcd * 8)), C::THREADS, C::LDS_BYTES, stream>>>(
-      base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),
-      reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset,
-      static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy, L.T, L.S, a.N, n_blocks, work_per_xcd, a.relu, a.out_f32);
+      base + L.a_offset + tb * L.S * RB * kPrepBlockBytes,
+      reinterpret_cast<const int32_t*>(base + L.gather_offset) + tb * L.S * 64,
+      reinterpret_cast<const int32_t*>(base + L.pi_out_offset) + tb * (32 * RB), base + L.zero_offset,
+      static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy, T, L.S, a.N, n_blocks, work_per_xcd, a.relu, a.out_f32);
   return hipGetLastError();
 }
 
@@ -358,8 +363,36 @@ inline int choose_variant(const PreparedArgs& a) {
   return 14;                                        // 256 columns, 64-column stages, 2 deep
 }
 
+// A layer whose wide blocks fill the chip a whole number of times plus a small remainder would spend a full
+// round on that remainder.  The tiles of the whole rounds keep the wide configuration; the remaining tiles are
+// launched behind them with 256-column blocks, twice as many workgroups of about half the duration, when
+// those fit one round.  Returns false when the shape does not ask for it.
+template <int DT, int RB>
+bool launch_split_rounds(const PreparedArgs& a, hipStream_t stream, hipError_t* result) {
+  const PreparedLayout L = prepared_layout(a.s);
+  const int nbw = (a.N + 511) / 512;
+  const int64_t wide_blocks = (int64_t)L.T * nbw;
+  if (a.N < 1024 || wide_blocks <= 256 || wide_blocks > 1024) return false;
+  const int rounds = (int)(wide_blocks / 256), rest = (int)(wide_blocks % 256);
+  if (rest == 0 || rest > 128) return false;
+  const int t_wide = 256 * rounds / nbw, t_rest = L.T - t_wide;
+  if (t_wide <= 0 || (int64_t)t_rest * ((a.N + 255) / 256) > 256) return false;
+  *result = launch_cfg<DT, RB, 512, 2, 2, 32>(a, stream, 0, t_wide);
+  if (*result != hipSuccess) return true;
+  if (RB <= 2 && L.S % 2 == 0) {
+    if constexpr (RB <= 2) *result = launch_cfg<DT, RB, 256, 4, 2, 32>(a, stream, t_wide, t_rest);
+  } else {
+    *result = launch_cfg<DT, RB, 256, 2, 2, 32>(a, stream, t_wide, t_rest);
+  }
+  return true;
+}
+
 template <int DT, int RB>
 hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
+  if (a.tile_variant == 0) {
+    hipError_t e;
+    if (launch_split_rounds<DT, RB>(a, stream, &e)) return e;
+  }
   switch (a.tile_variant ? a.tile_variant : choose_variant(a)) {
     case 1: return launch_cfg<DT, RB, 256, 2, 2>(a, stream);
     case 2: return launch_cfg<DT, RB, 256, 2, 3>(a, stream);

@@ -125,6 +125,16 @@ def test_prepared_small_all_variants(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 81), N, VARIANTS)
 
 
+@pytest.mark.parametrize("M,K,V,Kv,N,dtype", [
+    (2752, 1152, 32, 576, 2048, "f16"),      # 86 tiles x 4 wide blocks: 64 tiles in wide blocks, 22 in narrow ones
+    (11008, 1152, 128, 576, 2048, "bf16"),   # the same split with 128-row tiles
+    (5504, 1280, 64, 640, 1500, "f16"),      # 86 tiles x 3 wide blocks (ragged last block): 85 + 1
+])
+def test_prepared_remainder_tiles_in_a_second_launch(M, K, V, Kv, N, dtype):
+    """Layers whose wide blocks make whole rounds plus a small remainder are launched in two parts."""
+    _check(synth.small_case(M, K, V, Kv, N, dtype, 83), N, [0, 3, 16])
+
+
 def test_prepared_relu_identity():
     case = synth.small_case(128, 256, 64, 128, 72, "f16", 82)
     _check(case, 72, [0, 2, 3], relu=True)
