@@ -395,8 +395,10 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
                  (int)((flags & HINM_VARIANT_MASK) >> HINM_VARIANT_SHIFT), workspace, workspace_bytes};
   hipError_t e;
   // up to 16 columns: 16-row workgroups on the 16x16x64 form (measured faster than the 32-row kernel on every
-  // decode shape tried, by 8-10 % with 344 row blocks of 32 and by 15-37 % with 128); variant 11 pins it for any N
-  if (a.tile_variant == 11 || (a.tile_variant == 0 && N <= 16)) {
+  // decode shape tried, by 8-10 % with 344 row blocks of 32 and by 15-37 % with 128); variant 11 pins it for any N, 19 its form with
+  // the input rows resident in LDS (16 columns only)
+  if (a.tile_variant == 19 && !spmm_rows16_resident_supported(a)) return HINM_ERR_UNSUPPORTED;
+  if (a.tile_variant == 11 || a.tile_variant == 19 || (a.tile_variant == 0 && N <= 16)) {
     if ((N + 15) / 16 > 65535) return HINM_ERR_UNSUPPORTED;
     e = launch_spmm_rows16_prepared(a, stream);
   } else if (N <= 32 && (a.tile_variant == 0 || a.tile_variant == 12)) {  // variant 12 pins the 32-row skinny kernel

@@ -208,5 +208,7 @@ size_t skinny_prepared_workspace_bytes(const hinm_shape& s, int N);
 hipError_t launch_spmm_skinny_prepared(const PreparedArgs& a, hipStream_t stream);
 // few columns and few tiles: 16-row workgroups on the 16x16x64 form, reading the same prepared blocks
 hipError_t launch_spmm_rows16_prepared(const PreparedArgs& a, hipStream_t stream);
+// ... with all input rows resident in LDS (16 columns, K rows of 32 bytes beside the waves' slabs)
+bool spmm_rows16_resident_supported(const PreparedArgs& a);
 
 }  // namespace hinm

@@ -13,6 +13,7 @@
 #include "hinm_internal.h"
 #include "mfma_types.h"
 #include "prepared_layout.h"
+#include "direct_lds.h"
 
 namespace hinm {
 namespace {
@@ -54,17 +55,21 @@ __device__ __forceinline__ u32x8 read_b_operand(const uint8_t* slab, int i, int 
 // XMODE: 0 = any N / ld (element loads, slow), 1 = the 16 columns are inside N and rows are
 // 16-byte aligned, 2 = N == 1, 3 = N == 1 with the input vector staged in LDS (a 64-lane gather of 2-byte
 // elements from global memory costs the address unit one cycle per lane; the vector is small, so the
-// workgroup copies it whole, requested before everything else, and picks from LDS).  KB = steps whose loads
-// are issued together.  RBW = 1: the workgroup owns
-// 16 rows; RBW = 2: both halves of a 32-row block, which share the gathered input rows.
+// workgroup copies it whole, requested before everything else, and picks from LDS), 4 = 16 columns with all K
+// input rows resident in LDS (32 bytes each, copied once per workgroup with direct-to-LDS loads: rows
+// scattered by the input-channel order otherwise cost a whole 128-byte line each on the way from L2).
+// KB = steps whose loads are issued together.  RBW = 1: the workgroup owns 16 rows; RBW = 2: both halves of a
+// 32-row block, which share the gathered input rows; RBW = 4 (XMODE 4 only): two neighbouring 32-row blocks.
 template <int DT, int NW, int XMODE, int KB, int RBW>
 __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
     const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
     int V, int RB, int S64, int N, int K, bool relu, bool out_f32) {
   __shared__ __attribute__((aligned(16))) uint8_t slab_all[NW * kSlabBytes];
-  extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];  // XMODE 3: K elements + 8 zeros
-  static_assert(RBW * kRows * kCols * 4 <= kSlabBytes, "partial tiles must fit the slab");
+  extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];  // XMODE 3: K elements + 8 zeros; 4: K rows + a zero row
+  static_assert(XMODE == 4 || RBW * kRows * kCols * 4 <= kSlabBytes, "partial tiles must fit the slab");
+  static_assert(RBW <= 2 || XMODE == 4, "two 32-row blocks only with the resident input");
+  uint8_t* x_bytes = reinterpret_cast<uint8_t*>(x_lds);
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   // XMODE 3: this thread's 16-byte pieces of the input vector (requested now, written to LDS after the first
   // batch of weight loads has been issued); every wave passes the barrier exactly once
   u32x4 x_mine[kXPieces];
-  bool x_staged = XMODE != 3;
+  bool x_staged = XMODE != 3 && XMODE != 4;
   if constexpr (XMODE == 3) {
 #pragma unroll
     for (int r = 0; r < kXPieces; ++r) {
@@ -112,7 +117,22 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
       x_mine[r] = reinterpret_cast<const u32x4*>(X)[piece];
     }
   }
+  // XMODE 4: wave-wide copies of 32 rows x 32 bytes (lane l: row l / 2, half l % 2), requested before everything
+  // else; rows past K repeat the last row and are never addressed; the zero row sits behind the last copy
+  const int x_copies = (K + 31) / 32;
+  const int x_zero_row = 32 * x_copies;
+  if constexpr (XMODE == 4) {
+    for (int j = wave; j < x_copies; j += NW) {
+      const int r = min(32 * j + (lane >> 1), K - 1);
+      copy16_to_lds(X + (size_t)r * ldx + n0 + 8 * (lane & 1), x_bytes + (size_t)j * 1024);
+    }
+    if (threadIdx.x < 8) reinterpret_cast<uint32_t*>(x_bytes + (size_t)x_zero_row * 32)[threadIdx.x] = 0u;
+  }
   auto stage_x = [&]() {
+    if constexpr (XMODE == 4) {
+      wait_copies_outstanding<0>();  // this wave's copies (and its other loads) have landed
+      __syncthreads();               // ... and everyone's
+    }
     if constexpr (XMODE == 3) {
 #pragma unroll
       for (int r = 0; r < kXPieces; ++r) {
@@ -144,8 +164,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
       const size_t off = (size_t)min(sb + u, s_end - 1) * step_stride;
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb) {  // the second half sits 16 lanes further in the block
-        a_reg[u][rb] = *reinterpret_cast<const u32x4*>(a_lane + off + rb * 256);
-        const uint32_t word = *reinterpret_cast<const uint32_t*>(idx_lane + off + rb * 64);
+        // 16-row block rb: half rb % 2 of 32-row block rb / 2 (the second half sits 16 lanes further)
+        const size_t blk = (size_t)(rb >> 1) * kPrepBlockBytes;
+        a_reg[u][rb] = *reinterpret_cast<const u32x4*>(a_lane + off + blk + (rb & 1) * 256);
+        const uint32_t word = *reinterpret_cast<const uint32_t*>(idx_lane + off + blk + (rb & 1) * 64);
         idx_reg[u][rb] = (int)((q >> 1) ? (word >> 16) : (word & 0xFFFFu));
       }
     }
@@ -155,7 +177,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
       const uint16_t* xr = (col[u] >= 0) ? X + (size_t)col[u] * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
-      if constexpr (XMODE == 3) {
+      if constexpr (XMODE == 4) {
+        const uint8_t* xl = x_bytes + (size_t)(col[u] >= 0 ? col[u] : x_zero_row) * 32;
+        b_lo[u] = *reinterpret_cast<const u32x4*>(xl);
+        b_hi[u] = *reinterpret_cast<const u32x4*>(xl + 16);
+      } else if constexpr (XMODE == 3) {
         b_lo[u] = u32x4{(uint32_t)x_lds[col[u] >= 0 ? col[u] : K], 0, 0, 0};
         b_hi[u] = u32x4{0, 0, 0, 0};
       } else if constexpr (XMODE == 1) {
@@ -210,7 +236,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   // D layout: lane holds column lane % 16, rows 4 * (lane / 16) + reg.
   // (the slab is free now; its first kilobytes take this wave's partial tiles)
   wave_sync_lds();
-  float* partial = reinterpret_cast<float*>(slab);
+  // XMODE 4: the partial tiles (RBW kilobytes per wave) go where the input rows were, once nobody reads them
+  constexpr int kPartialStride = (XMODE == 4) ? RBW * kRows * kCols * 4 : kSlabBytes;
+  if constexpr (XMODE == 4) __syncthreads();
+  uint8_t* partial_all = (XMODE == 4) ? x_bytes : slab_all;
+  float* partial = reinterpret_cast<float*>(partial_all + wave * kPartialStride);
 #pragma unroll
   for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
@@ -222,7 +252,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     if (e < RBW * kRows * kCols) {
       float sum = 0.f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) sum += reinterpret_cast<const float*>(slab_all + w * kSlabBytes)[e];
+      for (int w = 0; w < NW; ++w) sum += reinterpret_cast<const float*>(partial_all + w * kPartialStride)[e];
       if (relu) sum = sum > 0.f ? sum : 0.f;
       const int c = e % kCols;
       if (n0 + c < N) {
@@ -271,6 +301,21 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t st
 #undef HINM_ROWS16
 }
 
+// The layer's input rows resident in LDS (XMODE 4): 16 columns, 64 rows per workgroup.
+inline size_t resident_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 1024 + 32; }
+
+template <int DT, int NW>
+void launch_resident(const PreparedArgs& a, const PreparedLayout& L, hipStream_t stream) {
+  constexpr auto kernel = spmm_rows16_prepared_kernel<DT, NW, 4, 4, 4>;
+  if (raise_lds_limit<kernel>(160 * 1024 - NW * kSlabBytes) != hipSuccess)
+    return;  // the error stays pending and is reported by the caller's hipGetLastError
+  const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
+  kernel<<<dim3(a.s.M / 64, 1), NW * 64, resident_lds_bytes(a.s.K), stream>>>(
+      base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),
+      reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset,
+      static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy, a.s.V, L.RB, L.S, a.N, a.s.K, a.relu, a.out_f32);
+}
+
 template <int DT, int RBW>
 void launch_waves(const PreparedArgs& a, hipStream_t stream) {
   const PreparedLayout L = prepared_layout(a.s);
@@ -284,6 +329,16 @@ void launch_waves(const PreparedArgs& a, hipStream_t stream) {
 
 template <int DT>
 void launch_dt(const PreparedArgs& a, hipStream_t stream) {
+  // 16 columns and a layer whose input fits in LDS beside the slabs: no gather from global memory at all.
+  // Each workgroup then owns 64 rows, so the layer needs enough of them to keep most of the chip streaming,
+  // and copying the 32 K bytes of input has to be small beside the workgroup's weights (11008 x 4096:
+  // 12.4 -> 10.3 us with 2048 kept columns, 7.4 -> 7.9 us with 1024).
+  const PreparedLayout L = prepared_layout(a.s);
+  if (spmm_rows16_resident_supported(a) && (a.tile_variant == 19 || (a.s.M / 64 >= 160 && L.S > 16))) {
+    if (L.S <= 16) launch_resident<DT, 4>(a, L, stream);
+    else launch_resident<DT, 8>(a, L, stream);
+    return;
+  }
   // Both halves of a 32-row block in one workgroup share the gathered input rows: worth it when those rows
   // are wide enough to matter and the grid still covers the chip in one round.
   const bool both = a.N > 4 && a.s.M / 32 >= 256;
@@ -292,6 +347,14 @@ void launch_dt(const PreparedArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
+
+bool spmm_rows16_resident_supported(const PreparedArgs& a) {
+  const PreparedLayout L = prepared_layout(a.s);
+  if (a.N != 16 || a.ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(a.X) & 15u) != 0) return false;
+  if (a.s.V % 64 != 0 || L.S > 32 || a.tile_variant == 11) return false;
+  const int NW = L.S <= 16 ? 4 : 8;
+  return resident_lds_bytes(a.s.K) + (size_t)NW * kSlabBytes <= 160 * 1024;
+}
 
 hipError_t launch_spmm_rows16_prepared(const PreparedArgs& a, hipStream_t stream) {
   if (a.s.dtype == HINM_F16) launch_dt<HINM_F16>(a, stream);

@@ -181,6 +181,33 @@ def test_prepared_sixteen_row_kernel_beyond_few_columns(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 89), N, [11], relu=True, identity=True)
 
 
+@pytest.mark.parametrize("M,K,V,Kv,dtype", [
+    (256, 512, 64, 256, "f16"),       # four steps: one wave per step
+    (384, 1000, 128, 504, "bf16"),    # K % 32 != 0, Kv % 64 != 0: clamped copies, padded kept columns
+    (128, 4096, 128, 2048, "f16"),    # 32 steps: the largest input that fits beside eight slabs
+    (192, 2048, 64, 1024, "bf16"),
+])
+def test_prepared_sixteen_columns_input_resident_in_lds(M, K, V, Kv, dtype):
+    case = synth.small_case(M, K, V, Kv, 16, dtype, 86)
+    _check(case, 16, [0, 11, 19])
+    _check(case, 16, [19], relu=True)
+    _check(case, 16, [19], identity=True)
+
+
+def test_prepared_input_resident_variant_refuses_what_it_cannot_hold():
+    import paper_2407_20496_amd as hinm
+    from tests import gpu_util as gu
+    for (M, K, V, Kv, N) in [(128, 8192, 128, 4096, 16),    # 256 KB of input rows
+                             (128, 512, 32, 256, 16),       # V % 64 != 0
+                             (128, 512, 64, 256, 8)]:       # not 16 columns
+        case = synth.small_case(M, K, V, Kv, N, "f16", 87)
+        p = gu.gpu_pack(case.weights(), "f16", V, Kv)
+        pr = gu.gpu_prepare(p, case.pi_in(), case.pi_out())
+        with pytest.raises(hinm.HinmError) as err:
+            gu.gpu_spmm_prepared(pr, case.activations(N), variant=19)
+        assert err.value.status == 5
+
+
 def test_prepared_few_columns_repeatable_and_needs_no_workspace():
     # partial tiles are added in a fixed order: repeated calls give identical bits
     import torch
