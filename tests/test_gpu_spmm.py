@@ -83,6 +83,28 @@ def test_spmm_small_all_kernels(M, K, V, Kv, N, dtype):
     _check_full(case, N, flags)
 
 
+@pytest.mark.parametrize("M,K,V,Kv,N,dtype", [
+    (128, 64, 32, 64, 40, "f16"),      # Kv == K: every column vector survives, only the 2:4 step prunes
+    (128, 256, 128, 128, 70, "bf16"),  # V == M: a single tile
+    (32, 8, 32, 8, 9, "f16"),          # the smallest layer the format allows: one tile, two groups of four
+    (64, 72, 32, 8, 1, "bf16"),        # one column, one NM byte per row
+    (256, 136, 64, 72, 16, "f16"),     # K and Kv are multiples of 8 only
+])
+def test_spmm_degenerate_shapes_canonical_and_prepared(M, K, V, Kv, N, dtype):
+    from tests import gpu_util as gu
+    case = synth.small_case(M, K, V, Kv, N, dtype, 63)
+    flags = [REF, 0] + ([GEMV] if N <= 16 else [])
+    _check_full(case, N, flags)
+    # the prepared form of the same layer gives the same bits as the canonical arrays
+    vals, nm, vec, _ = _oracle_pack(case)
+    p = gu.upload_packed(M, K, V, Kv, dtype, vals, nm, vec)
+    Xb = case.activations(N)
+    want = gu.gpu_spmm(p, Xb, case.pi_in(), case.pi_out(), REF)
+    got = gu.gpu_spmm_prepared(gu.gpu_prepare(p, case.pi_in(), case.pi_out()), Xb)
+    d = np.abs(orc.decode(got, dtype) - orc.decode(want, dtype))
+    assert np.all(d <= 2 * _ulp(orc.decode(want, dtype), dtype)), "prepared vs canonical beyond rounding of one sum order"
+
+
 def test_spmm_relu_identity_and_padded_leading_dimensions():
     case = synth.small_case(128, 256, 64, 128, 72, "f16", 61)
     _check_full(case, 72, [REF, SMFMAC], relu=True)
