@@ -130,6 +130,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
   __shared__ uint32_t wave_tot[kSelectThreads / 64];
   __shared__ unsigned long long s_prefix;
   __shared__ uint32_t s_need;
+  __shared__ uint32_t s_in_bin;  // keys in the bin the last pass chose
   const int t = blockIdx.x;
   const unsigned long long* key = reinterpret_cast<const unsigned long long*>(scores + (size_t)t * K);
   constexpr int kHeld = KPT > 0 ? KPT : 1;
@@ -203,34 +204,112 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
         }
         s_prefix = prefix | ((unsigned long long)(255 - (4 * lane + pick)) << shift);
         s_need = need - above;
+        s_in_bin = h[pick];
       }
     }
     __syncthreads();
     prefix = s_prefix;
     need = s_need;
     mask |= 0xFFull << shift;
+    // Every key of the chosen bin is wanted: the lower digits decide nothing any more.  (With distinct scores
+    // this happens after three or four of the eight passes.)
+    if (s_in_bin == need) break;
   }
-  const unsigned long long tau = prefix;  // Kv-th largest key
-  const uint32_t take_equal = need;       // keys equal to tau that survive (lowest columns)
+  // tau = the Kv-th largest key, or, after an early exit, its leading digits with zeros behind them: in both
+  // cases keys above tau survive, and of the keys equal to tau (only possible without an early exit) the
+  // take_equal lowest columns do.
+  const unsigned long long tau = prefix;
+  const uint32_t take_equal = need;
+  const bool ties_cut = s_in_bin != need;  // some keys equal to tau are dropped: their order matters
 
-  uint32_t eq_base = 0, kept_base = 0;
   int32_t* out = vec_idx + (size_t)t * Kv;
+  if constexpr (KPT > 0) {
+    // Keys in registers: one count per (chunk, wave), one scan of those <= 256 counts by the first wave, and
+    // every thread knows where its kept columns go -- two barriers per ranking instead of four per chunk.
+    constexpr int kWaves = kSelectThreads / 64;
+    __shared__ uint32_t cnt[KPT * kWaves];  // counts in (chunk, wave) order, then their exclusive prefix sums
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    auto scan_counts = [&]() {
+      __syncthreads();
+      if (threadIdx.x < 64) {
+        constexpr int kPer = (KPT * kWaves + 63) / 64;
+        uint32_t v[kPer], mine = 0;
 #pragma unroll
-  for (int c = 0; c < chunks; ++c) {
-    const int k = c * kSelectThreads + threadIdx.x;
-    const bool in = k < K;
-    unsigned long long u;
-    if constexpr (KPT > 0) u = held[c];
-    else u = in ? ordered_key(key[k]) : 0ull;
-    const bool gt = in && u > tau;
-    const bool eq = in && u == tau;
-    uint32_t eq_total, kept_total;
-    const uint32_t eq_rank = eq_base + block_exclusive_count(eq, wave_tot, eq_total);
-    const bool keep = gt || (eq && eq_rank < take_equal);
-    const uint32_t pos = kept_base + block_exclusive_count(keep, wave_tot, kept_total);
-    if (keep) out[pos] = k;
-    eq_base += eq_total;
-    kept_base += kept_total;
+        for (int q = 0; q < kPer; ++q) {
+          const int idx = kPer * lane + q;
+          v[q] = idx < KPT * kWaves ? cnt[idx] : 0u;
+          mine += v[q];
+        }
+        uint32_t incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const uint32_t o = (uint32_t)__shfl_up((int)incl, off);
+          if (lane >= off) incl += o;
+        }
+        uint32_t run = incl - mine;
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+          const int idx = kPer * lane + q;
+          if (idx < KPT * kWaves) cnt[idx] = run;
+          run += v[q];
+        }
+      }
+      __syncthreads();
+    };
+    uint32_t keep_bits = 0;  // bit c: this thread's key of chunk c survives
+    if (ties_cut) {          // uniform: rank the keys equal to tau by column
+#pragma unroll
+      for (int c = 0; c < KPT; ++c) {
+        const bool eq = (c * kSelectThreads + (int)threadIdx.x < K) && held[c] == tau;
+        const unsigned long long bal = __ballot(eq);
+        if (lane == 0) cnt[c * kWaves + wave] = (uint32_t)__popcll(bal);
+      }
+      scan_counts();
+#pragma unroll
+      for (int c = 0; c < KPT; ++c) {
+        const bool in = c * kSelectThreads + (int)threadIdx.x < K;
+        const bool eq = in && held[c] == tau;
+        const unsigned long long bal = __ballot(eq);
+        const uint32_t rank = cnt[c * kWaves + wave] + (uint32_t)__popcll(bal & below);
+        if (in && (held[c] > tau || (eq && rank < take_equal))) keep_bits |= 1u << c;
+      }
+      __syncthreads();  // cnt is rewritten below
+    } else {
+#pragma unroll
+      for (int c = 0; c < KPT; ++c)
+        if (c * kSelectThreads + (int)threadIdx.x < K && held[c] >= tau) keep_bits |= 1u << c;
+    }
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      const unsigned long long bal = __ballot((keep_bits >> c) & 1u);
+      if (lane == 0) cnt[c * kWaves + wave] = (uint32_t)__popcll(bal);
+    }
+    scan_counts();
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      const bool keep = (keep_bits >> c) & 1u;
+      const unsigned long long bal = __ballot(keep);
+      const uint32_t pos = cnt[c * kWaves + wave] + (uint32_t)__popcll(bal & below);
+      if (keep && pos < (uint32_t)Kv) out[pos] = c * kSelectThreads + (int)threadIdx.x;
+    }
+  } else {
+    uint32_t eq_base = 0, kept_base = 0;
+    for (int c = 0; c < chunks; ++c) {
+      const int k = c * kSelectThreads + threadIdx.x;
+      const bool in = k < K;
+      const unsigned long long u = in ? ordered_key(key[k]) : 0ull;
+      const bool gt = in && u > tau;
+      const bool eq = in && u == tau;
+      uint32_t eq_total, kept_total;
+      const uint32_t eq_rank = eq_base + block_exclusive_count(eq, wave_tot, eq_total);
+      const bool keep = gt || (eq && (!ties_cut || eq_rank < take_equal));
+      const uint32_t pos = kept_base + block_exclusive_count(keep, wave_tot, kept_total);
+      if (keep && pos < (uint32_t)Kv) out[pos] = k;
+      eq_base += eq_total;
+      kept_base += kept_total;
+    }
   }
 }
 
