@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kThreads) void spmm_vectors_kernel(
     const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * kYStride + b_chunk * 16);
     uint16_t* dst = Yh + out_row * ldy + n;
     if (n + 8 <= N) {
-      *reinterpret_cast<u32x4*>(dst) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
     } else if (n < N) {
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
       for (int e = 0; e < N - n; ++e) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
@@ -503,7 +503,7 @@ __global__ __launch_bounds__(NB / WC * 64) void spmm_vectors_dma_kernel(
     const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * C::Y_STRIDE + chunk * 16);
     uint16_t* dst = Yh + out_row * ldy + n;
     if (n + 8 <= N) {
-      *reinterpret_cast<u32x4*>(dst) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
     } else if (n < N) {
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
       for (int e = 0; e < N - n; ++e) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
