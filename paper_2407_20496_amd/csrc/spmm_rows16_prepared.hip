@@ -164,10 +164,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
       const size_t off = (size_t)min(sb + u, s_end - 1) * step_stride;
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb) {  // the second half sits 16 lanes further in the block
-        // 16-row block rb: half rb % 2 of 32-row block rb / 2 (the second half sits 16 lanes further)
+        // 16-row block rb: half rb % 2 of 32-row block rb / 2 (the second half sits 16 lanes further); the
+        // weights are read once, so they are kept from displacing the input rows and tables in the caches
         const size_t blk = (size_t)(rb >> 1) * kPrepBlockBytes;
-        a_reg[u][rb] = *reinterpret_cast<const u32x4*>(a_lane + off + blk + (rb & 1) * 256);
-        const uint32_t word = *reinterpret_cast<const uint32_t*>(idx_lane + off + blk + (rb & 1) * 64);
+        a_reg[u][rb] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a_lane + off + blk + (rb & 1) * 256));
+        const uint32_t word = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(idx_lane + off + blk + (rb & 1) * 64));
         idx_reg[u][rb] = (int)((q >> 1) ? (word >> 16) : (word & 0xFFFFu));
       }
     }

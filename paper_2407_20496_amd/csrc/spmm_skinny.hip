@@ -119,7 +119,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_skinny_kernel(
       const int g0 = 16 * s + 4 * q;  // this lane's four groups
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb) {
-        a_reg[u][rb] = *reinterpret_cast<const u32x4_a4*>(vrow + rb * vblock + 2 * g0);
+        a_reg[u][rb] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(vrow + rb * vblock + 2 * g0));  // read once
         const uint8_t* np = nrow + rb * nblock + (g0 >> 1);
         if (nm_pairs_aligned) idx_reg[u][rb] = *reinterpret_cast<const uint16_t*>(np);
         else idx_reg[u][rb] = (int)np[0] | ((int)np[1] << 8);
