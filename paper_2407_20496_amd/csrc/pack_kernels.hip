@@ -19,6 +19,8 @@
 namespace hinm {
 namespace {
 
+typedef uint32_t quad_t __attribute__((ext_vector_type(4)));  // 16 bytes for non-temporal stores
+
 constexpr int kScoreThreads = 256;
 constexpr int kSelectThreads = 1024;
 constexpr int kEmitThreads = 256;
@@ -380,8 +382,10 @@ __device__ __forceinline__ void emit_byte(const int32_t* __restrict__ vi, WAt w_
   uint2 packed;
   packed.x = (uint32_t)out[0] | ((uint32_t)out[1] << 16);
   packed.y = (uint32_t)out[2] | ((uint32_t)out[3] << 16);
-  *reinterpret_cast<uint2*>(vals_out) = packed;
-  *nm_out = (uint8_t)byte;
+  // written once and read by a later kernel: kept from displacing the rows of W in the caches
+  typedef uint32_t pair_t __attribute__((ext_vector_type(2)));
+  __builtin_nontemporal_store(pair_t{packed.x, packed.y}, reinterpret_cast<pair_t*>(vals_out));
+  __builtin_nontemporal_store((uint8_t)byte, nm_out);
 }
 
 template <bool SCORED>
@@ -418,7 +422,7 @@ __global__ __launch_bounds__(kEmitThreads) void gather_kernel(const uint16_t* __
   uint32_t o[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) o[q] = (uint32_t)wr[vi[2 * q]] | ((uint32_t)wr[vi[2 * q + 1]] << 16);
-  *reinterpret_cast<uint4*>(vals_v + (size_t)r * Kv + 8 * b) = make_uint4(o[0], o[1], o[2], o[3]);
+  __builtin_nontemporal_store(quad_t{o[0], o[1], o[2], o[3]}, reinterpret_cast<quad_t*>(vals_v + (size_t)r * Kv + 8 * b));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -518,7 +522,7 @@ __global__ __launch_bounds__(kEmitRowThreads<false>) void gather_rows_kernel(con
     uint32_t o[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) o[q] = (uint32_t)row[vi[2 * q]] | ((uint32_t)row[vi[2 * q + 1]] << 16);
-    *reinterpret_cast<uint4*>(vals_v + (size_t)r * Kv + 8 * b) = make_uint4(o[0], o[1], o[2], o[3]);
+    __builtin_nontemporal_store(quad_t{o[0], o[1], o[2], o[3]}, reinterpret_cast<quad_t*>(vals_v + (size_t)r * Kv + 8 * b));
   }
 }
 
