@@ -287,6 +287,10 @@ bool spmm_panel_prepared_preferred(const PreparedArgs& a) {
   if (!spmm_panel_prepared_supported(a)) return false;
   const PreparedLayout L = prepared_layout(a.s);
   if (L.T < 4) return false;
+  // a workgroup that stages a panel for one tile only pays the staging for nothing (3072 x 768 at N = 256:
+  // 13 us against 7 us for the tile kernel; at N = 512, with two tiles per workgroup, 8 against 9)
+  const int n_blocks = (a.N + kPanelCols - 1) / kPanelCols;
+  if (L.T <= (256 + n_blocks - 1) / n_blocks) return false;
   const int64_t wide_blocks = (int64_t)L.T * ((a.N + 511) / 512);
   if (L.RB == 4 && L.S >= 6 && a.N >= 1024 && wide_blocks >= 128) return false;
   return true;

@@ -52,8 +52,8 @@ __device__ __forceinline__ u32x8 read_b_operand(const uint8_t* slab, int i, int 
   return b;
 }
 
-// XMODE: 0 = any N / ld (element loads, slow), 1 = the 16 columns are inside N and rows are
-// 16-byte aligned, 2 = N == 1, 3 = N == 1 with the input vector staged in LDS (a 64-lane gather of 2-byte
+// XMODE: 0 = any N / ld (element loads, slow), 1 = rows are 16-byte aligned (ld % 8 == 0; columns beyond N
+// are computed on whatever the padding holds and never stored), 2 = N == 1, 3 = N == 1 with the input vector staged in LDS (a 64-lane gather of 2-byte
 // elements from global memory costs the address unit one cycle per lane; the vector is small, so the
 // workgroup copies it whole, requested before everything else, and picks from LDS), 4 = 16 columns with all K
 // input rows resident in LDS (32 bytes each, copied once per workgroup with direct-to-LDS loads: rows
@@ -193,8 +193,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
         const int c_hi = __builtin_amdgcn_ds_bpermute((32 + (lane >> 1)) * 4, col[u]);
         const uint16_t* r_lo = (c_lo >= 0) ? X + (size_t)c_lo * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
         const uint16_t* r_hi = (c_hi >= 0) ? X + (size_t)c_hi * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
-        b_lo[u] = *reinterpret_cast<const u32x4*>(r_lo + 8 * (lane & 1));
-        b_hi[u] = *reinterpret_cast<const u32x4*>(r_hi + 8 * (lane & 1));
+        // (the second half of a ragged last block may lie past the end of the row: its columns are beyond N
+        // then, and it is left out; whatever else a half holds beyond N never reaches a stored column)
+        const bool in_row = (lane & 1) == 0 || n0 + kCols <= (int)ldx;
+        b_lo[u] = in_row ? *reinterpret_cast<const u32x4*>(r_lo + 8 * (lane & 1)) : u32x4{0, 0, 0, 0};
+        b_hi[u] = in_row ? *reinterpret_cast<const u32x4*>(r_hi + 8 * (lane & 1)) : u32x4{0, 0, 0, 0};
       } else if constexpr (XMODE == 2) {
         b_lo[u] = u32x4{(uint32_t)xr[0], 0, 0, 0};
         b_hi[u] = u32x4{0, 0, 0, 0};
@@ -269,7 +272,6 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t st
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   auto x = static_cast<const uint16_t*>(a.X);
   const int col_blocks = (a.N + kCols - 1) / kCols;
-  const int full_blocks = (a.ldx % 8 == 0) ? a.N / kCols : 0;  // column blocks eligible for vector loads
 #define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF, LDS)                                                             \
   spmm_rows16_prepared_kernel<DT, NW, MODE, KB, RBW>                                                             \
       <<<dim3(a.s.M / (kRows * RBW), GRID_Y), NW * 64, LDS, stream>>>(                                           \
@@ -294,11 +296,9 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t st
     }
     return;
   }
-  if (full_blocks > 0) HINM_ROWS16(1, full_blocks, x, 0, 0);
-  if (col_blocks > full_blocks) {
-    const int off = full_blocks * kCols;  // ragged remainder: shift the column origin
-    HINM_ROWS16(0, col_blocks - full_blocks, x + off, off, 0);
-  }
+  // rows of X that start on 16-byte boundaries: vector loads for every block, the ragged last one included
+  if (a.ldx % 8 == 0) HINM_ROWS16(1, col_blocks, x, 0, 0);
+  else HINM_ROWS16(0, col_blocks, x, 0, 0);
 #undef HINM_ROWS16
 }
 

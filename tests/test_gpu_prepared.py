@@ -181,6 +181,26 @@ def test_prepared_sixteen_row_kernel_beyond_few_columns(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 89), N, [11], relu=True, identity=True)
 
 
+def test_prepared_few_columns_on_a_large_layer_and_garbage_in_the_padding():
+    """Up to 64 columns go to the 16-row kernel when the layer is large; columns of X beyond N (inside the
+    leading dimension) may hold anything."""
+    import torch
+    from tests import gpu_util as gu
+    case = synth.small_case(4096, 2048, 128, 1024, 40, "f16", 90)
+    _check(case, 40, [0, 11])
+    N, ld = 19, 24
+    case = synth.small_case(256, 1024, 64, 512, N, "bf16", 91)
+    p = gu.gpu_pack(case.weights(), case.dtype, case.V, case.Kv)
+    pr = gu.gpu_prepare(p, case.pi_in(), case.pi_out())
+    Xb = case.activations(N)
+    Xp = np.full((case.K, ld), 0x7FC0, dtype=np.uint16)     # NaN in every padding column
+    Xp[:, :N] = Xb
+    for variant in (0, 11, 12):
+        want = gu.gpu_spmm_prepared(pr, Xb, variant=variant, ldx=ld, ldy=ld)
+        got = gu.gpu_spmm_prepared(pr, Xb, variant=variant, ldx=ld, ldy=ld, X_dev=gu.dev_bits(Xp))
+        assert np.array_equal(got, want), f"variant {variant}"
+
+
 @pytest.mark.parametrize("M,K,V,Kv,dtype", [
     (256, 512, 64, 256, "f16"),       # four steps: one wave per step
     (384, 1000, 128, 504, "bf16"),    # K % 32 != 0, Kv % 64 != 0: clamped copies, padded kept columns
