@@ -291,6 +291,9 @@ bool spmm_panel_prepared_preferred(const PreparedArgs& a) {
   // 13 us against 7 us for the tile kernel; at N = 512, with two tiles per workgroup, 8 against 9)
   const int n_blocks = (a.N + kPanelCols - 1) / kPanelCols;
   if (L.T <= (256 + n_blocks - 1) / n_blocks) return false;
+  // column panel p runs on XCD p % 8: fewer than eight panels leave whole XCDs idle (3072 x 768 at N = 384,
+  // six panels: 13.3 us against 8.9 us)
+  if (n_blocks < 8) return false;
   const int64_t wide_blocks = (int64_t)L.T * ((a.N + 511) / 512);
   if (L.RB == 4 && L.S >= 6 && a.N >= 1024 && wide_blocks >= 128) return false;
   return true;

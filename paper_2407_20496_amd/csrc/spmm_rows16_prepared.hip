@@ -10,6 +10,7 @@
 // columns: the waves split the tile's steps into contiguous ranges, every wave issues all loads of a
 // batch of steps before it uses the first, gathered rows pass through a private LDS slab and come
 // back transposed, and the per-wave partial tiles are added in a fixed order through LDS.
+#include <cstdlib>
 #include "hinm_internal.h"
 #include "mfma_types.h"
 #include "prepared_layout.h"
@@ -145,6 +146,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     x_staged = true;
   };
 
+  const bool half_in_row = (lane & 1) == 0 || n0 + kCols <= (int)ldx;  // XMODE 1: this lane's half row exists
   for (int sb = s_begin; sb < s_end; sb += KB) {
     u32x4 a_reg[KB][RBW];
     int idx_reg[KB][RBW];
@@ -191,13 +193,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
         // rows scattered by the input-channel order costs.
         const int c_lo = __builtin_amdgcn_ds_bpermute((lane >> 1) * 4, col[u]);
         const int c_hi = __builtin_amdgcn_ds_bpermute((32 + (lane >> 1)) * 4, col[u]);
-        const uint16_t* r_lo = (c_lo >= 0) ? X + (size_t)c_lo * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
-        const uint16_t* r_hi = (c_hi >= 0) ? X + (size_t)c_hi * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
         // (the second half of a ragged last block may lie past the end of the row: its columns are beyond N
-        // then, and it is left out; whatever else a half holds beyond N never reaches a stored column)
-        const bool in_row = (lane & 1) == 0 || n0 + kCols <= (int)ldx;
-        b_lo[u] = in_row ? *reinterpret_cast<const u32x4*>(r_lo + 8 * (lane & 1)) : u32x4{0, 0, 0, 0};
-        b_hi[u] = in_row ? *reinterpret_cast<const u32x4*>(r_hi + 8 * (lane & 1)) : u32x4{0, 0, 0, 0};
+        // then, and it reads the zero row instead; whatever else a half holds beyond N never reaches a stored
+        // column)
+        const uint16_t* r_lo = (c_lo >= 0 && half_in_row) ? X + (size_t)c_lo * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
+        const uint16_t* r_hi = (c_hi >= 0 && half_in_row) ? X + (size_t)c_hi * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
+        b_lo[u] = *reinterpret_cast<const u32x4*>(r_lo + 8 * (lane & 1));
+        b_hi[u] = *reinterpret_cast<const u32x4*>(r_hi + 8 * (lane & 1));
       } else if constexpr (XMODE == 2) {
         b_lo[u] = u32x4{(uint32_t)xr[0], 0, 0, 0};
         b_hi[u] = u32x4{0, 0, 0, 0};
@@ -320,12 +322,26 @@ void launch_resident(const PreparedArgs& a, const PreparedLayout& L, hipStream_t
 template <int DT, int RBW>
 void launch_waves(const PreparedArgs& a, hipStream_t stream) {
   const PreparedLayout L = prepared_layout(a.s);
-  // one batch per wave where possible (every load of the wave in flight at once): waves x batch >= steps
-  if (L.S <= 4) launch_modes<DT, 1, 4, RBW>(a, L, stream);
-  else if (L.S <= 16) launch_modes<DT, 4, 4, RBW>(a, L, stream);
-  else if (L.S <= 32) launch_modes<DT, 8, 4, RBW>(a, L, stream);
-  else if (L.S <= 64) launch_modes<DT, 16, 4, RBW>(a, L, stream);
-  else launch_modes<DT, 16, 6, RBW>(a, L, stream);
+  // one batch per wave where possible (every load of the wave in flight at once): waves x batch >= steps ...
+  int nw = L.S <= 4 ? 1 : L.S <= 16 ? 4 : L.S <= 32 ? 8 : 16;
+  // ... but no more waves than the chip can hold at once: with many workgroups (several column blocks, or a
+  // tall layer) the parallelism is already there, and fewer waves per workgroup mean fewer partial tiles to
+  // sum and more of each wave's own loads in flight one after another (4096 x 4096 at N = 128, 2048
+  // workgroups: 32.8 us with eight waves, 22.7 us with one).  About eight waves per compute unit in total.
+  if (a.N > kCols) {
+    const int64_t wgs = (int64_t)(a.s.M / (kRows * RBW)) * ((a.N + kCols - 1) / kCols);
+    while (nw > 1 && wgs * nw > 2048) nw >>= 1;
+  }
+  const bool deep = L.S > 64;  // batches of six steps for long k loops
+  switch (nw) {
+    case 1: return launch_modes<DT, 1, 4, RBW>(a, L, stream);
+    case 2: return launch_modes<DT, 2, 4, RBW>(a, L, stream);
+    case 4: return launch_modes<DT, 4, 4, RBW>(a, L, stream);
+    case 8: return launch_modes<DT, 8, 4, RBW>(a, L, stream);
+    default:
+      if (deep) launch_modes<DT, 16, 6, RBW>(a, L, stream);
+      else launch_modes<DT, 16, 4, RBW>(a, L, stream);
+  }
 }
 
 template <int DT>

@@ -175,6 +175,11 @@ def test_prepared_few_columns(M, K, V, Kv, N, dtype):
     (192, 256, 96, 64, 40, "bf16"),       # a single step; 96-row tiles: three 32-row blocks
     (256, 8192, 128, 4416, 16, "bf16"),   # 69 steps: sixteen waves with more than one batch
     (8192, 256, 64, 128, 13, "f16"),      # 256 row blocks of 32: both halves of a block in one workgroup
+    # many workgroups: fewer waves each, several batches per wave
+    (4096, 1024, 128, 512, 136, "bf16"),  # 2304 workgroups: one wave walks all 8 steps
+    (2048, 2304, 128, 1152, 72, "f16"),   # 640 workgroups: two waves, 9 steps each
+    (8192, 512, 64, 384, 88, "bf16"),     # 1536 workgroups of 32 rows: one wave, 6 steps in two batches
+    (512, 4608, 32, 2304, 392, "f16"),    # 800 workgroups, 36 steps on two waves, ragged last block of 8
 ])
 def test_prepared_sixteen_row_kernel_beyond_few_columns(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 88), N, [11])
