@@ -398,18 +398,17 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
   // decode shape tried, by 8-10 % with 344 row blocks of 32 and by 15-37 % with 128); variant 11 pins it for any N, 19 its form with
   // the input rows resident in LDS (16 columns only)
   if (a.tile_variant == 19 && !spmm_rows16_resident_supported(a)) return HINM_ERR_UNSUPPORTED;
-  // ... and for up to 64 columns on every layer tried (one workgroup per 16 rows and 16 columns re-reads the
-  // weights for every column block and still wins: 11008 x 4096 at N = 64 29 vs 40 us, 1024 x 4096 6 vs 33 us),
-  // and up to 512 columns while its cost, which grows with M * Kv * ceil(N / 16), stays under the tile kernels'
-  // floor of one serial pass over the kept columns (about 16 us per 1024 of them): layers whose tiles cannot
-  // fill the chip.  Once X (K x N) outgrows one L2 the gathers cost half as much again.  The constants are
-  // fitted to timings of 84 (layer, N) pairs between 512 x 4608 and 8192 x 8192; the worst miss among them
-  // costs 15 %.
+  // ... and for up to 64 columns on every layer tried (one workgroup per 16..64 rows and 16 columns re-reads
+  // the weights for every column block and still wins: 11008 x 4096 at N = 64 23 vs 40 us, 1024 x 4096 6 vs
+  // 33 us), and up to 512 columns while its cost, which grows with M * Kv * ceil(N / 16), stays under the tile
+  // kernels' floor of one serial pass over the kept columns (about 15 us per 1024 of them, a little more per
+  // column on short passes): layers whose tiles cannot fill the chip.  The constants are fitted to timings of
+  // 42 (layer, N) pairs between 512 x 4608 and 8192 x 8192 and checked on 50 more at other N (worst miss 7 %).
   bool few_columns = N <= 64;
   if (!few_columns && N <= 512) {
     const double units = (double)shape->M * ((N + 15) / 16);
-    const double l2_factor = (double)shape->K * N * 2 > 3.5e6 ? 1.5 : 1.0;
-    few_columns = 2.5 + units * (0.22 * shape->Kv + 60.0) * 1e-6 * l2_factor < 3.0 + 16.0 * shape->Kv / 1024.0;
+    const double tile_floor_us = 1.0 + 15.0 * shape->Kv / 1024.0 + (shape->Kv <= 1024 ? 2.0 : 0.0);
+    few_columns = 2.5 + units * (0.14 * shape->Kv + 40.0) * 1e-6 < tile_floor_us;
   }
   if (a.tile_variant == 11 || a.tile_variant == 19 || (a.tile_variant == 0 && few_columns)) {
     if ((N + 15) / 16 > 65535) return HINM_ERR_UNSUPPORTED;

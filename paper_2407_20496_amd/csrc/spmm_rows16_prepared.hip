@@ -10,7 +10,6 @@
 // columns: the waves split the tile's steps into contiguous ranges, every wave issues all loads of a
 // batch of steps before it uses the first, gathered rows pass through a private LDS slab and come
 // back transposed, and the per-wave partial tiles are added in a fixed order through LDS.
-#include <cstdlib>
 #include "hinm_internal.h"
 #include "mfma_types.h"
 #include "prepared_layout.h"
@@ -60,16 +59,17 @@ __device__ __forceinline__ u32x8 read_b_operand(const uint8_t* slab, int i, int 
 // input rows resident in LDS (32 bytes each, copied once per workgroup with direct-to-LDS loads: rows
 // scattered by the input-channel order otherwise cost a whole 128-byte line each on the way from L2).
 // KB = steps whose loads are issued together.  RBW = 1: the workgroup owns 16 rows; RBW = 2: both halves of a
-// 32-row block, which share the gathered input rows; RBW = 4 (XMODE 4 only): two neighbouring 32-row blocks.
+// 32-row block, which share the gathered input rows; RBW = 4: two neighbouring 32-row blocks of one tile (V % 64 == 0).
 template <int DT, int NW, int XMODE, int KB, int RBW>
 __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
     const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
     int V, int RB, int S64, int N, int K, bool relu, bool out_f32) {
-  __shared__ __attribute__((aligned(16))) uint8_t slab_all[NW * kSlabBytes];
+  // a wave's slab holds its gathered rows, later its partial tiles (a kilobyte per 16 rows)
+  constexpr int kSlab = (XMODE != 4 && RBW * kRows * kCols * 4 > kSlabBytes) ? RBW * kRows * kCols * 4 : kSlabBytes;
+  __shared__ __attribute__((aligned(16))) uint8_t slab_all[NW * kSlab];
   extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];  // XMODE 3: K elements + 8 zeros; 4: K rows + a zero row
-  static_assert(XMODE == 4 || RBW * kRows * kCols * 4 <= kSlabBytes, "partial tiles must fit the slab");
-  static_assert(RBW <= 2 || XMODE == 4, "two 32-row blocks only with the resident input");
+  static_assert(RBW == 1 || RBW == 2 || RBW == 4, "half a 32-row block, one, or two neighbours");
   uint8_t* x_bytes = reinterpret_cast<uint8_t*>(x_lds);
 
   const int lane = threadIdx.x & 63;
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   const int s_begin = wave * per_wave;
   const int s_end = min(S64, s_begin + per_wave);  // this wave's contiguous range of steps (all steps are full: padded)
 
-  uint8_t* slab = slab_all + wave * kSlabBytes;
+  uint8_t* slab = slab_all + wave * kSlab;
   const int i = lane & 15;   // A row / B column inside the block
   const int q = lane >> 4;   // lane group: groups 4 q .. 4 q + 3 of the step = substep q / 2, quad q % 2
   // this lane's 16 bytes inside a (tile, step, row block) block of the prepared form, and its index word
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   // (the slab is free now; its first kilobytes take this wave's partial tiles)
   wave_sync_lds();
   // XMODE 4: the partial tiles (RBW kilobytes per wave) go where the input rows were, once nobody reads them
-  constexpr int kPartialStride = (XMODE == 4) ? RBW * kRows * kCols * 4 : kSlabBytes;
+  constexpr int kPartialStride = (XMODE == 4) ? RBW * kRows * kCols * 4 : kSlab;
   if constexpr (XMODE == 4) __syncthreads();
   uint8_t* partial_all = (XMODE == 4) ? x_bytes : slab_all;
   float* partial = reinterpret_cast<float*>(partial_all + wave * kPartialStride);
@@ -356,10 +356,16 @@ void launch_dt(const PreparedArgs& a, hipStream_t stream) {
     else launch_resident<DT, 8>(a, L, stream);
     return;
   }
-  // Both halves of a 32-row block in one workgroup share the gathered input rows: worth it when those rows
-  // are wide enough to matter and the grid still covers the chip in one round.
-  const bool both = a.N > 4 && a.s.M / 32 >= 256;
-  if (both) launch_waves<DT, 2>(a, stream);
+  // Several 16-row blocks in one workgroup share the gathered input rows: both halves of a 32-row block when
+  // the grid then still holds 256 workgroups (column blocks count: 4096 x 4096 at N = 128 22.8 -> 17.1 us), two
+  // neighbouring 32-row blocks under the same condition on layers of at least 2048 rows and beyond one column
+  // block (-> 13.0 us; 8192 x 8192 at N = 128 62.8 -> 47.8 us; with fewer rows the shorter grid loses: 768 x 3072
+  // at N = 384 9.2 -> 12.0 us).
+  const int64_t col_blocks = (a.N + kCols - 1) / kCols;
+  const bool quad = a.N > kCols && a.s.V % 64 == 0 && a.s.M >= 2048 && (a.s.M / 64) * col_blocks >= 256;
+  const bool both = a.N > 4 && (a.s.M / 32) * col_blocks >= 256;
+  if (quad) launch_waves<DT, 4>(a, stream);
+  else if (both) launch_waves<DT, 2>(a, stream);
   else launch_waves<DT, 1>(a, stream);
 }
 
