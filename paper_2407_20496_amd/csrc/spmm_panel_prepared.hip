@@ -258,14 +258,20 @@ hipError_t launch_waves(const PreparedArgs& a, int n_blocks, int tile_groups, hi
   return hipGetLastError();
 }
 
+// Workgroups per column panel.  The panel fills most of a compute unit's LDS, so a unit holds one workgroup,
+// and panel p runs on XCD p % 8 (32 units): the panels of the busiest XCD times the groups fit one round
+// (3072 x 768 at N = 768, twelve panels: 22 groups gave that XCD 44 workgroups, 13.6 us; 16 groups: 8.9 us).
+inline int panel_tile_groups(int n_blocks) {
+  const int panels_per_xcd = (n_blocks + 7) / 8;
+  return panels_per_xcd >= 32 ? 1 : 32 / panels_per_xcd;
+}
+
 template <int DT, int RB>
 hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
   const PreparedLayout L = prepared_layout(a.s);
   const int n_blocks = (a.N + kPanelCols - 1) / kPanelCols;
-  // about one workgroup per compute unit (the panel fills most of a unit's LDS)
-  int tile_groups = (256 + n_blocks - 1) / n_blocks;
+  int tile_groups = panel_tile_groups(n_blocks);
   if (tile_groups > L.T) tile_groups = L.T;
-  if (tile_groups < 1) tile_groups = 1;
   const int tiles_per_wg = (L.T + tile_groups - 1) / tile_groups;
   // one tile per wave when registers and LDS allow it: the waves then finish together
   if (RB <= 2 && tiles_per_wg > 8 && panel_lds_bytes(a.s.K, 12) <= 160 * 1024)
@@ -290,7 +296,7 @@ bool spmm_panel_prepared_preferred(const PreparedArgs& a) {
   // a workgroup that stages a panel for one tile only pays the staging for nothing (3072 x 768 at N = 256:
   // 13 us against 7 us for the tile kernel; at N = 512, with two tiles per workgroup, 8 against 9)
   const int n_blocks = (a.N + kPanelCols - 1) / kPanelCols;
-  if (L.T <= (256 + n_blocks - 1) / n_blocks) return false;
+  if (L.T <= panel_tile_groups(n_blocks)) return false;
   // column panel p runs on XCD p % 8: fewer than eight panels leave whole XCDs idle (3072 x 768 at N = 384,
   // six panels: 13.3 us against 8.9 us)
   if (n_blocks < 8) return false;
