@@ -264,7 +264,7 @@ hinm_status hinm_prepare(const hinm_shape* shape, const void* vals, const uint8_
 
 /* Same product as hinm_spmm, computed from a prepared layer (its pi_in / pi_out are the ones given
  * to hinm_prepare).  Flags: HINM_EPI_RELU, HINM_OUT_F32.
- * Few-column shapes (N <= 64, and small layers up to N = 1024) split each tile's kept columns over
+ * Few-column shapes (N <= 64, and small layers up to N = 2048) split each tile's kept columns over
  * the waves of one workgroup, which add their fp32 partial tiles in LDS in a fixed order, so results
  * are reproducible bit for bit.  Columns of X between N and ldx are never used in a result.
  * hinm_spmm_prepared_workspace gives the bytes of device workspace a shape needs: 0 for every kernel

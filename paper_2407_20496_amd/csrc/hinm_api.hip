@@ -400,17 +400,17 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
   if (a.tile_variant == 19 && !spmm_rows16_resident_supported(a)) return HINM_ERR_UNSUPPORTED;
   // ... and for up to 64 columns on every layer tried (one workgroup per 16..64 rows and 16 columns re-reads
   // the weights for every column block and still wins: 11008 x 4096 at N = 64 23 vs 40 us, 1024 x 4096 6 vs
-  // 33 us), and up to 1024 columns while its cost, which grows with M * Kv * ceil(N / 16), stays under the tile
+  // 33 us), and up to 2048 columns while its cost, which grows with M * Kv * ceil(N / 16), stays under the tile
   // kernels' floor of one serial pass over the kept columns (about 15 us per 1024 of them, a little more per
   // column on short passes): layers whose tiles cannot fill the chip.  The constants are fitted to timings of
   // 42 (layer, N) pairs between 512 x 4608 and 8192 x 8192 and checked on 50 more at other N (worst miss 7 %).
   bool few_columns = N <= 64;
-  if (!few_columns && N <= 1024) {
+  if (!few_columns && N <= 2048) {
     const double units = (double)shape->M * ((N + 15) / 16);
     const double tile_floor_us = 1.0 + 15.0 * shape->Kv / 1024.0 + (shape->Kv <= 1024 ? 2.0 : 0.0);
     // beyond 512 columns X (K x N) often outgrows one L2 and the gathers slow down (measured on small layers
-    // up to N = 4096: the kernel still wins to about 1024 columns on layers of a few hundred rows)
-    const double l2_factor = (N > 512 && (double)shape->K * N * 2 > 3.5e6) ? 1.5 : 1.0;
+    // up to N = 4096: the kernel still wins to 1024..2048 columns on layers of a few hundred rows)
+    const double l2_factor = (N > 512 && (double)shape->K * N * 2 > 3.5e6) ? (N > 1024 ? 2.0 : 1.5) : 1.0;
     few_columns = 2.5 + units * (0.14 * shape->Kv + 40.0) * 1e-6 * l2_factor < tile_floor_us;
   }
   if (a.tile_variant == 11 || a.tile_variant == 19 || (a.tile_variant == 0 && few_columns)) {
