@@ -60,16 +60,20 @@ __device__ __forceinline__ u32x8 read_b_operand(const uint8_t* slab, int i, int 
 // scattered by the input-channel order otherwise cost a whole 128-byte line each on the way from L2).
 // KB = steps whose loads are issued together.  RBW = 1: the workgroup owns 16 rows; RBW = 2: both halves of a
 // 32-row block, which share the gathered input rows; RBW = 4: two neighbouring 32-row blocks of one tile (V % 64 == 0).
-template <int DT, int NW, int XMODE, int KB, int RBW>
+// CB = 16-column blocks per workgroup (XMODE 1 only): with two, a step's weights, gather entries and cache
+// lines of input rows serve 32 columns.
+template <int DT, int NW, int XMODE, int KB, int RBW, int CB = 1>
 __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
     const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
     int V, int RB, int S64, int N, int K, bool relu, bool out_f32) {
   // a wave's slab holds its gathered rows, later its partial tiles (a kilobyte per 16 rows)
-  constexpr int kSlab = (XMODE != 4 && RBW * kRows * kCols * 4 > kSlabBytes) ? RBW * kRows * kCols * 4 : kSlabBytes;
+  constexpr int kTiles = RBW * CB;  // 16 x 16 output tiles of the workgroup
+  constexpr int kSlab = (XMODE != 4 && kTiles * kRows * kCols * 4 > kSlabBytes) ? kTiles * kRows * kCols * 4 : kSlabBytes;
   __shared__ __attribute__((aligned(16))) uint8_t slab_all[NW * kSlab];
   extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];  // XMODE 3: K elements + 8 zeros; 4: K rows + a zero row
   static_assert(RBW == 1 || RBW == 2 || RBW == 4, "half a 32-row block, one, or two neighbours");
+  static_assert(CB == 1 || (CB == 2 && XMODE == 1), "two column blocks only with paired-lane vector loads");
   uint8_t* x_bytes = reinterpret_cast<uint8_t*>(x_lds);
 
   const int lane = threadIdx.x & 63;
@@ -78,7 +82,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   const int t = row0 / V;
   const int rb32 = (row0 % V) / 32;     // 32-row block of the prepared form that holds these rows
   const int hf = (row0 % 32) / 16;      // ... and which half of it (0 when the workgroup owns both)
-  const int n0 = blockIdx.y * kCols;
+  const int n0 = blockIdx.y * (kCols * CB);
   const int per_wave = (S64 + NW - 1) / NW;
   const int s_begin = wave * per_wave;
   const int s_end = min(S64, s_begin + per_wave);  // this wave's contiguous range of steps (all steps are full: padded)
@@ -94,18 +98,20 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   const int32_t* gt = gather + (size_t)t * S64 * 64;
 
   // output rows of the epilogue, fetched early: element e = threadIdx.x + k * blockDim.x
-  constexpr int kOutPerThread = (RBW * kRows * kCols + NW * 64 - 1) / (NW * 64);
+  constexpr int kOutPerThread = (kTiles * kRows * kCols + NW * 64 - 1) / (NW * 64);
   int64_t out_row[kOutPerThread];
 #pragma unroll
   for (int k = 0; k < kOutPerThread; ++k) {
-    const int e = threadIdx.x + k * NW * 64;
-    const int row = min(e / kCols, RBW * kRows - 1);
+    const int e = min((int)threadIdx.x + k * NW * 64, kTiles * kRows * kCols - 1);
+    const int row = (e / kCols) % (RBW * kRows);  // element e: column block, then row, then column
     out_row[k] = out_rows[row0 + row];
   }
 
-  f32x4 acc[RBW];
+  f32x4 acc[CB][RBW];
 #pragma unroll
-  for (int rb = 0; rb < RBW; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) acc[cb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // XMODE 3: this thread's 16-byte pieces of the input vector (requested now, written to LDS after the first
   // batch of weight loads has been issued); every wave passes the barrier exactly once
@@ -146,12 +152,15 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     x_staged = true;
   };
 
-  const bool half_in_row = (lane & 1) == 0 || n0 + kCols <= (int)ldx;  // XMODE 1: this lane's half row exists
+  // XMODE 1: whether this lane's 16-byte piece of column block cb lies inside the row (ldx % 8 == 0)
+  bool piece_in_row[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) piece_in_row[cb] = n0 + kCols * cb + 8 * (lane & 1) + 8 <= (int)ldx;
   for (int sb = s_begin; sb < s_end; sb += KB) {
     u32x4 a_reg[KB][RBW];
     int idx_reg[KB][RBW];
     int col[KB];
-    u32x4 b_lo[KB], b_hi[KB];
+    u32x4 b_lo[KB][CB], b_hi[KB][CB];
     // Loads come back in issue order: the gather-table entries go first, the bulk weight stream is issued
     // behind them, and the input rows are requested as soon as their indices are known and arrive while the
     // weights are still streaming.  (Steps past the wave's range are clamped to its last step and zeroed
@@ -182,57 +191,62 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
       const uint16_t* xr = (col[u] >= 0) ? X + (size_t)col[u] * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
       if constexpr (XMODE == 4) {
         const uint8_t* xl = x_bytes + (size_t)(col[u] >= 0 ? col[u] : x_zero_row) * 32;
-        b_lo[u] = *reinterpret_cast<const u32x4*>(xl);
-        b_hi[u] = *reinterpret_cast<const u32x4*>(xl + 16);
+        b_lo[u][0] = *reinterpret_cast<const u32x4*>(xl);
+        b_hi[u][0] = *reinterpret_cast<const u32x4*>(xl + 16);
       } else if constexpr (XMODE == 3) {
-        b_lo[u] = u32x4{(uint32_t)x_lds[col[u] >= 0 ? col[u] : K], 0, 0, 0};
-        b_hi[u] = u32x4{0, 0, 0, 0};
+        b_lo[u][0] = u32x4{(uint32_t)x_lds[col[u] >= 0 ? col[u] : K], 0, 0, 0};
+        b_hi[u][0] = u32x4{0, 0, 0, 0};
       } else if constexpr (XMODE == 1) {
         // Lanes 2 j and 2 j + 1 fetch the two 16-byte halves of one row (rows j and 32 + j of the step):
         // neighbouring lanes then fall into one cache line, which halves the tag look-ups that a gather of
         // rows scattered by the input-channel order costs.
         const int c_lo = __builtin_amdgcn_ds_bpermute((lane >> 1) * 4, col[u]);
         const int c_hi = __builtin_amdgcn_ds_bpermute((32 + (lane >> 1)) * 4, col[u]);
-        // (the second half of a ragged last block may lie past the end of the row: its columns are beyond N
-        // then, and it reads the zero row instead; whatever else a half holds beyond N never reaches a stored
-        // column)
-        const uint16_t* r_lo = (c_lo >= 0 && half_in_row) ? X + (size_t)c_lo * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
-        const uint16_t* r_hi = (c_hi >= 0 && half_in_row) ? X + (size_t)c_hi * ldx + n0 : reinterpret_cast<const uint16_t*>(zeros);
-        b_lo[u] = *reinterpret_cast<const u32x4*>(r_lo + 8 * (lane & 1));
-        b_hi[u] = *reinterpret_cast<const u32x4*>(r_hi + 8 * (lane & 1));
+        // (a piece of a ragged last block may lie past the end of the row: its columns are beyond N then, and
+        // it reads the zero row instead; whatever else a piece holds beyond N never reaches a stored column)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          const uint16_t* r_lo = (c_lo >= 0 && piece_in_row[cb]) ? X + (size_t)c_lo * ldx + n0 + kCols * cb : reinterpret_cast<const uint16_t*>(zeros);
+          const uint16_t* r_hi = (c_hi >= 0 && piece_in_row[cb]) ? X + (size_t)c_hi * ldx + n0 + kCols * cb : reinterpret_cast<const uint16_t*>(zeros);
+          b_lo[u][cb] = *reinterpret_cast<const u32x4*>(r_lo + 8 * (lane & 1));
+          b_hi[u][cb] = *reinterpret_cast<const u32x4*>(r_hi + 8 * (lane & 1));
+        }
       } else if constexpr (XMODE == 2) {
-        b_lo[u] = u32x4{(uint32_t)xr[0], 0, 0, 0};
-        b_hi[u] = u32x4{0, 0, 0, 0};
+        b_lo[u][0] = u32x4{(uint32_t)xr[0], 0, 0, 0};
+        b_hi[u][0] = u32x4{0, 0, 0, 0};
       } else {
         uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           if (n0 + e < N) w[e >> 1] |= (uint32_t)xr[e] << (16 * (e & 1));
-        b_lo[u] = u32x4{w[0], w[1], w[2], w[3]};
-        b_hi[u] = u32x4{w[4], w[5], w[6], w[7]};
+        b_lo[u][0] = u32x4{w[0], w[1], w[2], w[3]};
+        b_hi[u][0] = u32x4{w[4], w[5], w[6], w[7]};
       }
     }
     // phase 4: multiply
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
       const bool live = sb + u < s_end;  // wave-uniform
-      if constexpr (XMODE == 1) {  // half rows: see the loads
-        *reinterpret_cast<u32x4*>(slab + slab_row_offset(lane >> 1) + 16 * (lane & 1)) = b_lo[u];
-        *reinterpret_cast<u32x4*>(slab + slab_row_offset(32 + (lane >> 1)) + 16 * (lane & 1)) = b_hi[u];
-      } else {
-        uint8_t* wr = slab + slab_row_offset(lane);
-        *reinterpret_cast<u32x4*>(wr) = b_lo[u];
-        *reinterpret_cast<u32x4*>(wr + 16) = b_hi[u];
-      }
-      wave_sync_lds();
-      u32x8 b = read_b_operand(slab, i, q);
-      if (!live) b = u32x8{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-      for (int rb = 0; rb < RBW; ++rb) {
-        const u32x4 a = live ? a_reg[u][rb] : u32x4{0, 0, 0, 0};
-        acc[rb] = smfmac_16x16x64<DT, 0>(a, b, acc[rb], idx_reg[u][rb]);
+      for (int cb = 0; cb < CB; ++cb) {
+        if constexpr (XMODE == 1) {  // half rows: see the loads
+          *reinterpret_cast<u32x4*>(slab + slab_row_offset(lane >> 1) + 16 * (lane & 1)) = b_lo[u][cb];
+          *reinterpret_cast<u32x4*>(slab + slab_row_offset(32 + (lane >> 1)) + 16 * (lane & 1)) = b_hi[u][cb];
+        } else {
+          uint8_t* wr = slab + slab_row_offset(lane);
+          *reinterpret_cast<u32x4*>(wr) = b_lo[u][cb];
+          *reinterpret_cast<u32x4*>(wr + 16) = b_hi[u][cb];
+        }
+        wave_sync_lds();
+        u32x8 b = read_b_operand(slab, i, q);
+        if (!live) b = u32x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+          const u32x4 a = live ? a_reg[u][rb] : u32x4{0, 0, 0, 0};
+          acc[cb][rb] = smfmac_16x16x64<DT, 0>(a, b, acc[cb][rb], idx_reg[u][rb]);
+        }
+        wave_sync_lds();
       }
-      wave_sync_lds();
     }
   }
 
@@ -242,25 +256,27 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   // D layout: lane holds column lane % 16, rows 4 * (lane / 16) + reg.
   // (the slab is free now; its first kilobytes take this wave's partial tiles)
   wave_sync_lds();
-  // XMODE 4: the partial tiles (RBW kilobytes per wave) go where the input rows were, once nobody reads them
-  constexpr int kPartialStride = (XMODE == 4) ? RBW * kRows * kCols * 4 : kSlab;
+  // XMODE 4: the partial tiles (a kilobyte each) go where the input rows were, once nobody reads them
+  constexpr int kPartialStride = (XMODE == 4) ? kTiles * kRows * kCols * 4 : kSlab;
   if constexpr (XMODE == 4) __syncthreads();
   uint8_t* partial_all = (XMODE == 4) ? x_bytes : slab_all;
   float* partial = reinterpret_cast<float*>(partial_all + wave * kPartialStride);
 #pragma unroll
-  for (int rb = 0; rb < RBW; ++rb)
+  for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-    for (int reg = 0; reg < 4; ++reg) partial[(16 * rb + 4 * q + reg) * kCols + i] = acc[rb][reg];
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int reg = 0; reg < 4; ++reg) partial[(16 * (cb * RBW + rb) + 4 * q + reg) * kCols + i] = acc[cb][rb][reg];
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < kOutPerThread; ++k) {
     const int e = threadIdx.x + k * NW * 64;
-    if (e < RBW * kRows * kCols) {
+    if (e < kTiles * kRows * kCols) {
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < NW; ++w) sum += reinterpret_cast<const float*>(partial_all + w * kPartialStride)[e];
       if (relu) sum = sum > 0.f ? sum : 0.f;
-      const int c = e % kCols;
+      const int c = kCols * (e / (RBW * kRows * kCols)) + e % kCols;
       if (n0 + c < N) {
         if (out_f32) static_cast<float*>(Y)[out_row[k] * ldy + n0 + c] = sum;
         else static_cast<uint16_t*>(Y)[out_row[k] * ldy + n0 + c] = float_to_bits<DT>(sum);
@@ -270,12 +286,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
 }
 
 template <int DT, int NW, int KB, int RBW>
-void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t stream) {
+void launch_modes(const PreparedArgs& a, const PreparedLayout& L, bool two_blocks, hipStream_t stream) {
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   auto x = static_cast<const uint16_t*>(a.X);
   const int col_blocks = (a.N + kCols - 1) / kCols;
-#define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF, LDS)                                                             \
-  spmm_rows16_prepared_kernel<DT, NW, MODE, KB, RBW>                                                             \
+#define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF, LDS) HINM_ROWS16_CB(MODE, 1, GRID_Y, X_PTR, Y_OFF, LDS)
+#define HINM_ROWS16_CB(MODE, CBV, GRID_Y, X_PTR, Y_OFF, LDS)                                                     \
+  spmm_rows16_prepared_kernel<DT, NW, MODE, KB, RBW, CBV>                                                        \
       <<<dim3(a.s.M / (kRows * RBW), GRID_Y), NW * 64, LDS, stream>>>(                                           \
           base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),                           \
           reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset, X_PTR, a.ldx,          \
@@ -299,9 +316,16 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, hipStream_t st
     return;
   }
   // rows of X that start on 16-byte boundaries: vector loads for every block, the ragged last one included
+  if constexpr (NW <= 8) {  // (sixteen waves leave 128 registers per lane: not enough for two blocks)
+    if (two_blocks && a.ldx % 8 == 0) {
+      HINM_ROWS16_CB(1, 2, (col_blocks + 1) / 2, x, 0, 0);
+      return;
+    }
+  }
   if (a.ldx % 8 == 0) HINM_ROWS16(1, col_blocks, x, 0, 0);
   else HINM_ROWS16(0, col_blocks, x, 0, 0);
 #undef HINM_ROWS16
+#undef HINM_ROWS16_CB
 }
 
 // The layer's input rows resident in LDS (XMODE 4): 16 columns, 64 rows per workgroup.
@@ -319,28 +343,64 @@ void launch_resident(const PreparedArgs& a, const PreparedLayout& L, hipStream_t
       static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy, a.s.V, L.RB, L.S, a.N, a.s.K, a.relu, a.out_f32);
 }
 
-template <int DT, int RBW>
-void launch_waves(const PreparedArgs& a, hipStream_t stream) {
+// Launch shape beyond the template choice by N: 16-row blocks per workgroup, waves, column blocks per workgroup.
+struct Rows16Plan {
+  int rbw;
+  int nw;
+  bool two_blocks;
+};
+
+Rows16Plan plan_rows16(const PreparedArgs& a) {
   const PreparedLayout L = prepared_layout(a.s);
+  Rows16Plan p;
+  // Several 16-row blocks in one workgroup share the gathered input rows: both halves of a 32-row block when
+  // the grid then still holds 256 workgroups (column blocks count: 4096 x 4096 at N = 128 22.8 -> 17.1 us), two
+  // neighbouring 32-row blocks under the same condition on layers of at least 2048 rows and beyond one column
+  // block (-> 13.0 us; 8192 x 8192 at N = 128 62.8 -> 47.8 us; with fewer rows the shorter grid loses: 768 x 3072
+  // at N = 384 9.2 -> 12.0 us).
+  const int64_t col_blocks = (a.N + kCols - 1) / kCols;
+  const bool quad = a.N > kCols && a.s.V % 64 == 0 && a.s.M >= 2048 && (a.s.M / 64) * col_blocks >= 256;
+  const bool both = a.N > 4 && (a.s.M / 32) * col_blocks >= 256;
+  p.rbw = quad ? 4 : both ? 2 : 1;
   // one batch per wave where possible (every load of the wave in flight at once): waves x batch >= steps ...
-  int nw = L.S <= 4 ? 1 : L.S <= 16 ? 4 : L.S <= 32 ? 8 : 16;
-  // ... but no more waves than the chip can hold at once: with many workgroups (several column blocks, or a
-  // tall layer) the parallelism is already there, and fewer waves per workgroup mean fewer partial tiles to
-  // sum and more of each wave's own loads in flight one after another (4096 x 4096 at N = 128, 2048
-  // workgroups: 32.8 us with eight waves, 22.7 us with one).  About eight waves per compute unit in total.
+  const int nw_steps = L.S <= 4 ? 1 : L.S <= 16 ? 4 : L.S <= 32 ? 8 : 16;
+  p.nw = nw_steps;
+  p.two_blocks = false;
   if (a.N > kCols) {
-    const int64_t wgs = (int64_t)(a.s.M / (kRows * RBW)) * ((a.N + kCols - 1) / kCols);
-    while (nw > 1 && wgs * nw > 2048) nw >>= 1;
+    // ... but no more waves than the chip can hold at once: with many workgroups (several column blocks, or
+    // a tall layer) the parallelism is already there, and fewer waves per workgroup mean fewer partial tiles
+    // to sum and more of each wave's own loads in flight one after another (4096 x 4096 at N = 128, 2048
+    // workgroups: 32.8 us with eight waves, 22.7 us with one).  About eight waves per compute unit in total.
+    const int64_t row_wgs = a.s.M / (kRows * p.rbw);
+    // Two column blocks per workgroup: a step's weights, gather entries and the cache lines of its input rows
+    // then serve 32 columns (11008 x 4096 at N = 128 42.3 -> 31.1 us, 8192 x 8192 at N = 256 89.5 -> 69.3 us).
+    // It needs long k loops and a grid that still covers most of the chip (2048 x 2048 with 512 kept columns
+    // at N = 128: 4.7 -> 5.9 us; 4096 x 4096 at N = 64, 128 workgroups: 7.9 -> 9.5 us).
+    p.two_blocks = a.ldx % 8 == 0 && L.S >= 16 && row_wgs * ((col_blocks + 1) / 2) >= 160;
+    const int64_t wgs = row_wgs * (p.two_blocks ? (col_blocks + 1) / 2 : col_blocks);
+    while (p.nw > 1 && wgs * p.nw > 2048) p.nw >>= 1;
+    if (p.two_blocks && p.nw > 8) {  // sixteen waves leave too few registers for two blocks
+      p.two_blocks = false;
+      p.nw = nw_steps;
+      while (p.nw > 1 && row_wgs * col_blocks * p.nw > 2048) p.nw >>= 1;
+    }
   }
+  return p;
+}
+
+template <int DT, int RBW>
+void launch_waves(const PreparedArgs& a, const Rows16Plan& plan, hipStream_t stream) {
+  const PreparedLayout L = prepared_layout(a.s);
+  const bool two_blocks = plan.two_blocks;
   const bool deep = L.S > 64;  // batches of six steps for long k loops
-  switch (nw) {
-    case 1: return launch_modes<DT, 1, 4, RBW>(a, L, stream);
-    case 2: return launch_modes<DT, 2, 4, RBW>(a, L, stream);
-    case 4: return launch_modes<DT, 4, 4, RBW>(a, L, stream);
-    case 8: return launch_modes<DT, 8, 4, RBW>(a, L, stream);
+  switch (plan.nw) {
+    case 1: return launch_modes<DT, 1, 4, RBW>(a, L, two_blocks, stream);
+    case 2: return launch_modes<DT, 2, 4, RBW>(a, L, two_blocks, stream);
+    case 4: return launch_modes<DT, 4, 4, RBW>(a, L, two_blocks, stream);
+    case 8: return launch_modes<DT, 8, 4, RBW>(a, L, two_blocks, stream);
     default:
-      if (deep) launch_modes<DT, 16, 6, RBW>(a, L, stream);
-      else launch_modes<DT, 16, 4, RBW>(a, L, stream);
+      if (deep) launch_modes<DT, 16, 6, RBW>(a, L, false, stream);
+      else launch_modes<DT, 16, 4, RBW>(a, L, false, stream);
   }
 }
 
@@ -356,20 +416,15 @@ void launch_dt(const PreparedArgs& a, hipStream_t stream) {
     else launch_resident<DT, 8>(a, L, stream);
     return;
   }
-  // Several 16-row blocks in one workgroup share the gathered input rows: both halves of a 32-row block when
-  // the grid then still holds 256 workgroups (column blocks count: 4096 x 4096 at N = 128 22.8 -> 17.1 us), two
-  // neighbouring 32-row blocks under the same condition on layers of at least 2048 rows and beyond one column
-  // block (-> 13.0 us; 8192 x 8192 at N = 128 62.8 -> 47.8 us; with fewer rows the shorter grid loses: 768 x 3072
-  // at N = 384 9.2 -> 12.0 us).
-  const int64_t col_blocks = (a.N + kCols - 1) / kCols;
-  const bool quad = a.N > kCols && a.s.V % 64 == 0 && a.s.M >= 2048 && (a.s.M / 64) * col_blocks >= 256;
-  const bool both = a.N > 4 && (a.s.M / 32) * col_blocks >= 256;
-  if (quad) launch_waves<DT, 4>(a, stream);
-  else if (both) launch_waves<DT, 2>(a, stream);
-  else launch_waves<DT, 1>(a, stream);
+  const Rows16Plan plan = plan_rows16(a);
+  if (plan.rbw == 4) launch_waves<DT, 4>(a, plan, stream);
+  else if (plan.rbw == 2) launch_waves<DT, 2>(a, plan, stream);
+  else launch_waves<DT, 1>(a, plan, stream);
 }
 
 }  // namespace
+
+bool spmm_rows16_prepared_two_blocks(const PreparedArgs& a) { return plan_rows16(a).two_blocks; }
 
 bool spmm_rows16_resident_supported(const PreparedArgs& a) {
   const PreparedLayout L = prepared_layout(a.s);

@@ -179,7 +179,8 @@ def test_prepared_few_columns(M, K, V, Kv, N, dtype):
     (4096, 1024, 128, 512, 136, "bf16"),  # 2304 workgroups: one wave walks all 8 steps
     (2048, 2304, 128, 1152, 72, "f16"),   # 640 workgroups: two waves, 9 steps each
     (8192, 512, 64, 384, 88, "bf16"),     # 1536 workgroups of 32 rows: one wave, 6 steps in two batches
-    (512, 4608, 32, 2304, 392, "f16"),    # 800 workgroups, 36 steps on two waves, ragged last block of 8
+    (512, 4608, 32, 2304, 392, "f16"),    # 36 steps, two column blocks per workgroup, ragged last block of 8
+    (4096, 2048, 128, 1024, 72, "bf16"),  # 64-row workgroups with two column blocks; the last pair holds 8 columns
 ])
 def test_prepared_sixteen_row_kernel_beyond_few_columns(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 88), N, [11])
@@ -193,14 +194,19 @@ def test_prepared_few_columns_on_a_large_layer_and_garbage_in_the_padding():
     from tests import gpu_util as gu
     case = synth.small_case(4096, 2048, 128, 1024, 40, "f16", 90)
     _check(case, 40, [0, 11])
-    N, ld = 19, 24
-    case = synth.small_case(256, 1024, 64, 512, N, "bf16", 91)
+    _padding_may_hold_anything(synth.small_case(256, 1024, 64, 512, 19, "bf16", 91), 19, 24, (0, 11, 12))
+    # two column blocks per workgroup: the second pair covers columns 32..47 of the row and nothing beyond
+    _padding_may_hold_anything(synth.small_case(2048, 2304, 128, 1152, 40, "f16", 92), 40, 48, (0, 11))
+
+
+def _padding_may_hold_anything(case, N, ld, variants):
+    from tests import gpu_util as gu
     p = gu.gpu_pack(case.weights(), case.dtype, case.V, case.Kv)
     pr = gu.gpu_prepare(p, case.pi_in(), case.pi_out())
     Xb = case.activations(N)
     Xp = np.full((case.K, ld), 0x7FC0, dtype=np.uint16)     # NaN in every padding column
     Xp[:, :N] = Xb
-    for variant in (0, 11, 12):
+    for variant in variants:
         want = gu.gpu_spmm_prepared(pr, Xb, variant=variant, ldx=ld, ldy=ld)
         got = gu.gpu_spmm_prepared(pr, Xb, variant=variant, ldx=ld, ldy=ld, X_dev=gu.dev_bits(Xp))
         assert np.array_equal(got, want), f"variant {variant}"
