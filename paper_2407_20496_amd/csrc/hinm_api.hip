@@ -411,8 +411,9 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
     // beyond 512 columns X (K x N) often outgrows one L2 and the gathers slow down (measured on small layers
     // up to N = 4096: the kernel still wins to 1024..2048 columns on layers of a few hundred rows)
     const double l2_factor = (N > 512 && (double)shape->K * N * 2 > 3.5e6) ? (N > 1024 ? 2.0 : 1.5) : 1.0;
-    // (with two column blocks per workgroup the kernel measured 19-34 % faster)
-    const double pair_factor = spmm_rows16_prepared_two_blocks(a) ? 0.78 : 1.0;
+    // (with two column blocks per workgroup the kernel measured 19-34 % faster, with four as much again)
+    const int blocks_per_wg = spmm_rows16_prepared_blocks_per_wg(a);
+    const double pair_factor = blocks_per_wg == 4 ? 0.58 : blocks_per_wg == 2 ? 0.78 : 1.0;
     few_columns = 2.5 + units * (0.14 * shape->Kv + 40.0) * 1e-6 * l2_factor * pair_factor < tile_floor_us;
   }
   if (a.tile_variant == 11 || a.tile_variant == 19 || (a.tile_variant == 0 && few_columns)) {

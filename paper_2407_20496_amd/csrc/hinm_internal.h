@@ -210,6 +210,6 @@ hipError_t launch_spmm_skinny_prepared(const PreparedArgs& a, hipStream_t stream
 hipError_t launch_spmm_rows16_prepared(const PreparedArgs& a, hipStream_t stream);
 // ... with all input rows resident in LDS (16 columns, K rows of 32 bytes beside the waves' slabs)
 bool spmm_rows16_resident_supported(const PreparedArgs& a);
-bool spmm_rows16_prepared_two_blocks(const PreparedArgs& a);  // 32 columns per workgroup chosen for this call
+int spmm_rows16_prepared_blocks_per_wg(const PreparedArgs& a);  // 16-column blocks per workgroup chosen for this call (1, 2, 4)
 
 }  // namespace hinm

@@ -60,8 +60,8 @@ __device__ __forceinline__ u32x8 read_b_operand(const uint8_t* slab, int i, int 
 // scattered by the input-channel order otherwise cost a whole 128-byte line each on the way from L2).
 // KB = steps whose loads are issued together.  RBW = 1: the workgroup owns 16 rows; RBW = 2: both halves of a
 // 32-row block, which share the gathered input rows; RBW = 4: two neighbouring 32-row blocks of one tile (V % 64 == 0).
-// CB = 16-column blocks per workgroup (XMODE 1 only): with two, a step's weights, gather entries and cache
-// lines of input rows serve 32 columns.
+// CB = 16-column blocks per workgroup (XMODE 1 only): with two or four, a step's weights, gather entries and
+// cache lines of input rows serve 32 or 64 columns.
 template <int DT, int NW, int XMODE, int KB, int RBW, int CB = 1>
 __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
     const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
   __shared__ __attribute__((aligned(16))) uint8_t slab_all[NW * kSlab];
   extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];  // XMODE 3: K elements + 8 zeros; 4: K rows + a zero row
   static_assert(RBW == 1 || RBW == 2 || RBW == 4, "half a 32-row block, one, or two neighbours");
-  static_assert(CB == 1 || (CB == 2 && XMODE == 1), "two column blocks only with paired-lane vector loads");
+  static_assert(CB == 1 || ((CB == 2 || CB == 4) && XMODE == 1), "several column blocks only with paired-lane vector loads");
   uint8_t* x_bytes = reinterpret_cast<uint8_t*>(x_lds);
 
   const int lane = threadIdx.x & 63;
@@ -286,13 +286,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_rows16_prepared_kernel(
 }
 
 template <int DT, int NW, int KB, int RBW>
-void launch_modes(const PreparedArgs& a, const PreparedLayout& L, bool two_blocks, hipStream_t stream) {
+void launch_modes(const PreparedArgs& a, const PreparedLayout& L, int blocks_per_wg, hipStream_t stream) {
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   auto x = static_cast<const uint16_t*>(a.X);
   const int col_blocks = (a.N + kCols - 1) / kCols;
-#define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF, LDS) HINM_ROWS16_CB(MODE, 1, GRID_Y, X_PTR, Y_OFF, LDS)
-#define HINM_ROWS16_CB(MODE, CBV, GRID_Y, X_PTR, Y_OFF, LDS)                                                     \
-  spmm_rows16_prepared_kernel<DT, NW, MODE, KB, RBW, CBV>                                                        \
+#define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF, LDS) HINM_ROWS16_CB(MODE, 1, KB, GRID_Y, X_PTR, Y_OFF, LDS)
+#define HINM_ROWS16_CB(MODE, CBV, KBV, GRID_Y, X_PTR, Y_OFF, LDS)                                                \
+  spmm_rows16_prepared_kernel<DT, NW, MODE, KBV, RBW, CBV>                                                       \
       <<<dim3(a.s.M / (kRows * RBW), GRID_Y), NW * 64, LDS, stream>>>(                                           \
           base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),                           \
           reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset, X_PTR, a.ldx,          \
@@ -316,9 +316,13 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, bool two_block
     return;
   }
   // rows of X that start on 16-byte boundaries: vector loads for every block, the ragged last one included
-  if constexpr (NW <= 8) {  // (sixteen waves leave 128 registers per lane: not enough for two blocks)
-    if (two_blocks && a.ldx % 8 == 0) {
-      HINM_ROWS16_CB(1, 2, (col_blocks + 1) / 2, x, 0, 0);
+  if constexpr (NW <= 8) {  // (sixteen waves leave 128 registers per lane: not enough for several blocks)
+    if (blocks_per_wg == 4 && a.ldx % 8 == 0) {  // (batches of two steps: four blocks of input rows per step)
+      HINM_ROWS16_CB(1, 4, 2, (col_blocks + 3) / 4, x, 0, 0);
+      return;
+    }
+    if (blocks_per_wg == 2 && a.ldx % 8 == 0) {
+      HINM_ROWS16_CB(1, 2, KB, (col_blocks + 1) / 2, x, 0, 0);
       return;
     }
   }
@@ -347,7 +351,7 @@ void launch_resident(const PreparedArgs& a, const PreparedLayout& L, hipStream_t
 struct Rows16Plan {
   int rbw;
   int nw;
-  bool two_blocks;
+  int blocks_per_wg;  // 16-column blocks: 1, 2 or 4
 };
 
 Rows16Plan plan_rows16(const PreparedArgs& a) {
@@ -365,22 +369,26 @@ Rows16Plan plan_rows16(const PreparedArgs& a) {
   // one batch per wave where possible (every load of the wave in flight at once): waves x batch >= steps ...
   const int nw_steps = L.S <= 4 ? 1 : L.S <= 16 ? 4 : L.S <= 32 ? 8 : 16;
   p.nw = nw_steps;
-  p.two_blocks = false;
+  p.blocks_per_wg = 1;
   if (a.N > kCols) {
     // ... but no more waves than the chip can hold at once: with many workgroups (several column blocks, or
     // a tall layer) the parallelism is already there, and fewer waves per workgroup mean fewer partial tiles
     // to sum and more of each wave's own loads in flight one after another (4096 x 4096 at N = 128, 2048
     // workgroups: 32.8 us with eight waves, 22.7 us with one).  About eight waves per compute unit in total.
     const int64_t row_wgs = a.s.M / (kRows * p.rbw);
-    // Two column blocks per workgroup: a step's weights, gather entries and the cache lines of its input rows
-    // then serve 32 columns (11008 x 4096 at N = 128 42.3 -> 31.1 us, 8192 x 8192 at N = 256 89.5 -> 69.3 us).
-    // It needs long k loops and a grid that still covers most of the chip (2048 x 2048 with 512 kept columns
-    // at N = 128: 4.7 -> 5.9 us; 4096 x 4096 at N = 64, 128 workgroups: 7.9 -> 9.5 us).
-    p.two_blocks = a.ldx % 8 == 0 && L.S >= 16 && row_wgs * ((col_blocks + 1) / 2) >= 160;
-    const int64_t wgs = row_wgs * (p.two_blocks ? (col_blocks + 1) / 2 : col_blocks);
+    // Two or four column blocks per workgroup: a step's weights, gather entries and the 128-byte cache lines of
+    // its input rows then serve 32 or 64 columns (11008 x 4096 at N = 128 42.3 -> 31.1 -> 24.8 us, 8192 x 8192
+    // at N = 256 89.5 -> 69.3 -> 45.0 us).  It needs long k loops and a grid that still covers most of the chip
+    // (2048 x 2048 with 512 kept columns at N = 128: 4.7 -> 5.9 us with two; 4096 x 4096 at N = 64, 128
+    // workgroups left: 7.9 -> 9.5 us).
+    if (a.ldx % 8 == 0 && L.S >= 16) {
+      if (row_wgs * ((col_blocks + 3) / 4) >= 160) p.blocks_per_wg = 4;
+      else if (row_wgs * ((col_blocks + 1) / 2) >= 160) p.blocks_per_wg = 2;
+    }
+    const int64_t wgs = row_wgs * ((col_blocks + p.blocks_per_wg - 1) / p.blocks_per_wg);
     while (p.nw > 1 && wgs * p.nw > 2048) p.nw >>= 1;
-    if (p.two_blocks && p.nw > 8) {  // sixteen waves leave too few registers for two blocks
-      p.two_blocks = false;
+    if (p.blocks_per_wg > 1 && p.nw > 8) {  // sixteen waves leave too few registers for several blocks
+      p.blocks_per_wg = 1;
       p.nw = nw_steps;
       while (p.nw > 1 && row_wgs * col_blocks * p.nw > 2048) p.nw >>= 1;
     }
@@ -391,16 +399,16 @@ Rows16Plan plan_rows16(const PreparedArgs& a) {
 template <int DT, int RBW>
 void launch_waves(const PreparedArgs& a, const Rows16Plan& plan, hipStream_t stream) {
   const PreparedLayout L = prepared_layout(a.s);
-  const bool two_blocks = plan.two_blocks;
+  const int blocks = plan.blocks_per_wg;
   const bool deep = L.S > 64;  // batches of six steps for long k loops
   switch (plan.nw) {
-    case 1: return launch_modes<DT, 1, 4, RBW>(a, L, two_blocks, stream);
-    case 2: return launch_modes<DT, 2, 4, RBW>(a, L, two_blocks, stream);
-    case 4: return launch_modes<DT, 4, 4, RBW>(a, L, two_blocks, stream);
-    case 8: return launch_modes<DT, 8, 4, RBW>(a, L, two_blocks, stream);
+    case 1: return launch_modes<DT, 1, 4, RBW>(a, L, blocks, stream);
+    case 2: return launch_modes<DT, 2, 4, RBW>(a, L, blocks, stream);
+    case 4: return launch_modes<DT, 4, 4, RBW>(a, L, blocks, stream);
+    case 8: return launch_modes<DT, 8, 4, RBW>(a, L, blocks, stream);
     default:
-      if (deep) launch_modes<DT, 16, 6, RBW>(a, L, false, stream);
-      else launch_modes<DT, 16, 4, RBW>(a, L, false, stream);
+      if (deep) launch_modes<DT, 16, 6, RBW>(a, L, 1, stream);
+      else launch_modes<DT, 16, 4, RBW>(a, L, 1, stream);
   }
 }
 
@@ -424,7 +432,7 @@ void launch_dt(const PreparedArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-bool spmm_rows16_prepared_two_blocks(const PreparedArgs& a) { return plan_rows16(a).two_blocks; }
+int spmm_rows16_prepared_blocks_per_wg(const PreparedArgs& a) { return plan_rows16(a).blocks_per_wg; }
 
 bool spmm_rows16_resident_supported(const PreparedArgs& a) {
   const PreparedLayout L = prepared_layout(a.s);

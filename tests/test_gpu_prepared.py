@@ -181,6 +181,8 @@ def test_prepared_few_columns(M, K, V, Kv, N, dtype):
     (8192, 512, 64, 384, 88, "bf16"),     # 1536 workgroups of 32 rows: one wave, 6 steps in two batches
     (512, 4608, 32, 2304, 392, "f16"),    # 36 steps, two column blocks per workgroup, ragged last block of 8
     (4096, 2048, 128, 1024, 72, "bf16"),  # 64-row workgroups with two column blocks; the last pair holds 8 columns
+    (4096, 2048, 128, 1024, 200, "f16"),  # 64-row workgroups with four column blocks; the last four hold 8 columns
+    (2048, 2304, 32, 1152, 136, "bf16"),  # 32-row tiles, four column blocks, 18 steps
 ])
 def test_prepared_sixteen_row_kernel_beyond_few_columns(M, K, V, Kv, N, dtype):
     _check(synth.small_case(M, K, V, Kv, N, dtype, 88), N, [11])
