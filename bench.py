@@ -81,6 +81,8 @@ def main():
                     help="also run a plain 256 MiB device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--kernel-us", type=float, default=None,
                     help="icp / ocp workloads: average duration of the cost kernel from a rocprofv3 summary, to price it")
+    ap.add_argument("--columns", type=int, default=0,
+                    help="run the workload's layer(s) at this many columns instead of its own N (not a BASELINE configuration)")
     ap.add_argument("--ld-pad", type=int, default=0,
                     help="add this many elements (a multiple of 8) to the leading dimensions of X and Y")
     ap.add_argument("--no-graph", action="store_true",
@@ -116,6 +118,9 @@ def main():
               + " vectors-<any of the latter>", file=sys.stderr)
         sys.exit(2)
     c = wl[args.workload]
+    if args.columns:   # the same layer at another number of columns (batched decode: 32 .. 512)
+        import dataclasses
+        c = dataclasses.replace(c, N=args.columns, name=f"{c.name} at N = {args.columns}")
     chain = args.workload == "c4"
     N = c.N
     n_layers = 2 if chain else 1
@@ -267,11 +272,13 @@ def main():
     else:
         roofline["kernel"] = ("spmm_skinny_kernel" if N <= 16 or c.V % 32 else
                               "spmm_tile_dma_kernel" if c.Kv % 64 == 0 else "spmm_tile_kernel")
+    if args.columns:   # not one of the profiled configurations: the library picks the kernel by shape
+        roofline["kernel"] = None
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
             tr = json.load(f).get(args.workload if not args.canonical else args.workload + "-canonical")
-        if tr and mem_bound:
+        if tr and mem_bound and not args.columns:
             roofline["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
             roofline["traffic_source"] = tr.get("source")
     except (OSError, ValueError):

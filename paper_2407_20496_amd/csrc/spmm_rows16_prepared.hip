@@ -382,7 +382,7 @@ Rows16Plan plan_rows16(const PreparedArgs& a) {
     // (2048 x 2048 with 512 kept columns at N = 128: 4.7 -> 5.9 us with two; 4096 x 4096 at N = 64, 128
     // workgroups left: 7.9 -> 9.5 us).
     if (a.ldx % 8 == 0 && L.S >= 16) {
-      if (row_wgs * ((col_blocks + 3) / 4) >= 160) p.blocks_per_wg = 4;
+      if (col_blocks >= 3 && row_wgs * ((col_blocks + 3) / 4) >= 160) p.blocks_per_wg = 4;
       else if (row_wgs * ((col_blocks + 1) / 2) >= 160) p.blocks_per_wg = 2;
     }
     const int64_t wgs = row_wgs * ((col_blocks + p.blocks_per_wg - 1) / p.blocks_per_wg);
