@@ -403,17 +403,20 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
   // 33 us), and up to 2048 columns while its cost, which grows with M * Kv * ceil(N / 16), stays under the tile
   // kernels' floor of one serial pass over the kept columns (about 15 us per 1024 of them, a little more per
   // column on short passes): layers whose tiles cannot fill the chip.  The constants are fitted to timings of
-  // 42 (layer, N) pairs between 512 x 4608 and 8192 x 8192 and checked on 50 more at other N (worst miss 7 %).
+  // 42 (layer, N) pairs between 512 x 4608 and 8192 x 8192 and checked on some 250 more at other N.
   bool few_columns = N <= 64;
   if (!few_columns && N <= 2048) {
     const double units = (double)shape->M * ((N + 15) / 16);
-    const double tile_floor_us = 1.0 + 15.0 * shape->Kv / 1024.0 + (shape->Kv <= 1024 ? 2.0 : 0.0);
-    // beyond 512 columns X (K x N) often outgrows one L2 and the gathers slow down (measured on small layers
-    // up to N = 4096: the kernel still wins to 1024..2048 columns on layers of a few hundred rows)
-    const double l2_factor = (N > 512 && (double)shape->K * N * 2 > 3.5e6) ? (N > 1024 ? 2.0 : 1.5) : 1.0;
-    // (with two column blocks per workgroup the kernel measured 19-34 % faster, with four as much again)
+    // the tile kernels' pass: 15 us per 1024 kept columns, and on short passes 2 us more, 4 with 128-row tiles
+    const double tile_floor_us = 1.0 + 15.0 * shape->Kv / 1024.0 + (shape->Kv <= 1024 ? (shape->V >= 128 ? 4.0 : 2.0) : 0.0);
+    // with two column blocks per workgroup the 16-row kernel measured 19-34 % faster, with four as much again
     const int blocks_per_wg = spmm_rows16_prepared_blocks_per_wg(a);
     const double pair_factor = blocks_per_wg == 4 ? 0.58 : blocks_per_wg == 2 ? 0.78 : 1.0;
+    // beyond 512 columns X (K x N) often outgrows one L2 and the gathers slow down, those that use a quarter
+    // or half of each cache line first (measured on small layers up to N = 4096: the kernel still wins to
+    // 1024..2048 columns on layers of a few hundred rows)
+    const bool x_beyond_l2 = (double)shape->K * N * 2 > 3.5e6;
+    const double l2_factor = !x_beyond_l2 ? 1.0 : N > 1024 ? 2.0 : (N > 512 && blocks_per_wg < 4) ? 1.5 : 1.0;
     few_columns = 2.5 + units * (0.14 * shape->Kv + 40.0) * 1e-6 * l2_factor * pair_factor < tile_floor_us;
   }
   if (a.tile_variant == 11 || a.tile_variant == 19 || (a.tile_variant == 0 && few_columns)) {

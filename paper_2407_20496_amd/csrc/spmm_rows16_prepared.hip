@@ -378,10 +378,11 @@ Rows16Plan plan_rows16(const PreparedArgs& a) {
     const int64_t row_wgs = a.s.M / (kRows * p.rbw);
     // Two or four column blocks per workgroup: a step's weights, gather entries and the 128-byte cache lines of
     // its input rows then serve 32 or 64 columns (11008 x 4096 at N = 128 42.3 -> 31.1 -> 24.8 us, 8192 x 8192
-    // at N = 256 89.5 -> 69.3 -> 45.0 us).  It needs long k loops and a grid that still covers most of the chip
-    // (2048 x 2048 with 512 kept columns at N = 128: 4.7 -> 5.9 us with two; 4096 x 4096 at N = 64, 128
-    // workgroups left: 7.9 -> 9.5 us).
-    if (a.ldx % 8 == 0 && L.S >= 16) {
+    // at N = 256 89.5 -> 69.3 -> 45.0 us).  It needs a grid that still covers most of the chip (160 workgroups;
+    // with 96..159 it measured slower: 4096 x 4096 at N = 64, 128 workgroups left, 7.9 -> 9.5 us) and at least
+    // eight steps (from there on never slower under that condition; 8192 x 1024 with 512 kept columns at
+    // N = 256: 17.7 -> 13.5 us).
+    if (a.ldx % 8 == 0 && L.S >= 8) {
       if (col_blocks >= 3 && row_wgs * ((col_blocks + 3) / 4) >= 160) p.blocks_per_wg = 4;
       else if (row_wgs * ((col_blocks + 1) / 2) >= 160) p.blocks_per_wg = 2;
     }
