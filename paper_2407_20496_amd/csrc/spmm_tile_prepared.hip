@@ -345,13 +345,28 @@ hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream, int tile_base =
 // copies better and cost 40 % more LDS reads per MFMA: they win wherever a compute unit holds a single
 // workgroup and the layer is not large enough to be bound by LDS and L2 throughput (measured on the
 // encoder, convolution and MLP shapes: 5 to 20 %; the 16384 x 16384 x 8192 layer is 2 % slower with them).
+// A round of workgroups is one serial pass over the kept columns however few workgroups it holds, and a pass of
+// a 512-column block costs about 1.35 passes of a 256-column block (128-row tiles, whose workgroups sit alone
+// on a compute unit).  True when the 256-column blocks need fewer passes by that count (11008 x 4096 at
+// N = 1280: 430 narrow blocks in two rounds, 74 us, against 258 wide blocks in two rounds, 89 us).
+inline bool narrow_blocks_save_rounds(const PreparedLayout& L, int64_t wide_blocks, int64_t blocks) {
+  return L.RB == 4 && (double)((blocks + 255) / 256) < ((wide_blocks + 255) / 256) * 1.35;
+}
+
 inline int choose_variant(const PreparedArgs& a) {
   const PreparedLayout L = prepared_layout(a.s);
   const int64_t wide_blocks = (int64_t)L.T * ((a.N + 511) / 512);
   // 512 columns, 64-column stages, 2 deep: sixteen 32-column waves up to a few rounds of workgroups, eight
   // 64-column waves beyond
-  if (a.N >= 1024 && wide_blocks >= 256) return wide_blocks <= 1024 ? 16 : 3;
   const int64_t blocks = (int64_t)L.T * ((a.N + 255) / 256);
+  if (a.N >= 1024 && wide_blocks >= 256 && !narrow_blocks_save_rounds(L, wide_blocks, blocks))
+    return wide_blocks <= 1024 ? 16 : 3;
+  // ... and wherever they save rounds of workgroups: a round is one serial pass over the kept columns however
+  // few workgroups it holds, and a pass of a 512-column block costs about 1.35 passes of a 256-column block
+  // (11008 x 4096 at N = 768: 258 narrow blocks, two rounds, 72 us; 172 wide blocks, one round, 47 us).  For
+  // 128-row tiles only, whose workgroups sit alone on a compute unit: with 32-row tiles several share one and
+  // 384 of them are no two rounds (768 x 3072, V = 32, at N = 4096: the narrow blocks stay 2 us ahead).
+  if (a.N > 256 && L.RB == 4 && L.S > 8 && ((wide_blocks + 255) / 256) * 1.35 < (double)((blocks + 255) / 256)) return 16;
   // short k loops: 32-column stages, 2 deep, so that several workgroups share a compute unit and cover each
   // other's start-up and epilogue (128-row tiles with at least half as many wide blocks as units; or many
   // workgroups per unit)
@@ -373,6 +388,7 @@ bool launch_split_rounds(const PreparedArgs& a, hipStream_t stream, hipError_t* 
   const int nbw = (a.N + 511) / 512;
   const int64_t wide_blocks = (int64_t)L.T * nbw;
   if (a.N < 1024 || wide_blocks <= 256 || wide_blocks > 1024) return false;
+  if (narrow_blocks_save_rounds(L, wide_blocks, (int64_t)L.T * ((a.N + 255) / 256))) return false;
   const int rounds = (int)(wide_blocks / 256), rest = (int)(wide_blocks % 256);
   if (rest == 0 || rest > 128) return false;
   const int t_wide = 256 * rounds / nbw, t_rest = L.T - t_wide;
