@@ -407,8 +407,11 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
   bool few_columns = N <= 64;
   if (!few_columns && N <= 2048) {
     const double units = (double)shape->M * ((N + 15) / 16);
-    // the tile kernels' pass: 15 us per 1024 kept columns, and on short passes 2 us more, 4 with 128-row tiles
-    const double tile_floor_us = 1.0 + 15.0 * shape->Kv / 1024.0 + (shape->Kv <= 1024 ? (shape->V >= 128 ? 4.0 : 2.0) : 0.0);
+    // the tile kernels' pass: 15 us per 1024 kept columns (12 with tiles of up to 64 rows: smaller stages,
+    // 128-column stages where the step count is even), and on short passes 2 us more, 4 with 128-row tiles
+    const double tile_floor_us =
+        shape->V >= 96 ? 1.0 + 15.0 * shape->Kv / 1024.0 + (shape->Kv <= 1024 ? (shape->V >= 128 ? 4.0 : 2.0) : 0.0)
+                       : 2.0 + 12.0 * shape->Kv / 1024.0 + (shape->Kv <= 1024 ? 2.0 : 0.0);
     // with two column blocks per workgroup the 16-row kernel measured 19-34 % faster, with four as much again
     const int blocks_per_wg = spmm_rows16_prepared_blocks_per_wg(a);
     const double pair_factor = blocks_per_wg == 4 ? 0.58 : blocks_per_wg == 2 ? 0.78 : 1.0;
