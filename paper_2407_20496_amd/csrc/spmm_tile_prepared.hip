@@ -375,6 +375,10 @@ inline int choose_variant(const PreparedArgs& a) {
   // At most one workgroup per compute unit: every stage then waits one full memory round trip, and
   // 128-column stages halve the number of round trips.
   if (L.RB <= 2 && L.S % 2 == 0 && blocks <= 256) return 13;
+  // 128-row tiles, more than one round of 256-column blocks but at most two, and 512-column blocks not chosen
+  // above: with 32-column stages two workgroups share a compute unit and all of them run at once
+  // (11008 x 4096 at N = 1280, 430 blocks: 74 -> 63 us; 16384 x 4096 with 512 kept columns at N = 768: 26 -> 22 us)
+  if (L.RB == 4 && blocks > 256 && blocks <= 512) return 17;
   return 14;                                        // 256 columns, 64-column stages, 2 deep
 }
 
