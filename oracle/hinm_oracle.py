@@ -380,6 +380,23 @@ def product_entries(Wh_bits: np.ndarray, X_bits: np.ndarray, dtype: str,
     return out
 
 
+def product_rows(Wh_rows_bits: np.ndarray, X_bits: np.ndarray, dtype: str,
+                 pi_in: Optional[Sequence[int]], relu: bool = False) -> np.ndarray:
+    """Whole rows of the same product for a subset of W's rows, in binary64, for layers too large
+    for the matrix form with explicit permutation matrices:
+        out[a, n] = sum_k W_HiNM[r_a, k] * X[pi_in[k], n]
+    where Wh_rows_bits holds the rows r_a of W_HiNM.  Row k of (P_in X) is row pi_in[k] of X by
+    the definition of P_in, so the 0/1 matrix product is written as that row selection; the
+    contraction is one binary64 matrix product.  Entry (pi_out[r_a], n) of P_out (W_HiNM (P_in X))
+    is out[a, n]: the caller looks the value up there."""
+    Wr = decode(Wh_rows_bits, dtype)
+    K = Wr.shape[1]
+    pin = np.arange(K) if pi_in is None else np.asarray(pi_in)
+    Xp = decode(np.asarray(X_bits)[pin], dtype)          # (P_in X)[k, :] = X[pi_in[k], :]
+    Y = Wr @ Xp
+    return np.maximum(Y, 0.0) if relu else Y
+
+
 def chain(layers, X_bits: np.ndarray, dtype: str, acc=np.float32) -> np.ndarray:
     """Consecutive layers with independent channel orders (Section 3.2,
     "maintaining layer consistency"): every layer is (Wh_bits, pi_in, pi_out,

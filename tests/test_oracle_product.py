@@ -136,6 +136,29 @@ def test_product_entries_matches_matrix_form():
     assert Yr.min() == 0.0
 
 
+def test_product_rows_matches_matrix_form_and_entry_form():
+    # the row-subset form used for sampled checks of large layers: against the explicit permutation
+    # matrices (binary64) and against the element-by-element sum, with orders that are not involutions
+    case = synth.small_case(64, 96, 16, 48, 24, "bf16", 29)
+    _, _, _, _, Wh = _packed(case)
+    Xb = case.activations()
+    pi_in, pi_out = case.pi_in(), case.pi_out()
+    assert not np.array_equal(pi_in[pi_in], np.arange(case.K))
+    Y = orc.product(Wh, Xb, "bf16", pi_in, pi_out, acc=np.float64)
+    rows = np.array([0, 5, 17, 40, 63])
+    got = orc.product_rows(Wh[rows], Xb, "bf16", pi_in)
+    assert got.dtype == np.float64 and got.shape == (5, 24)
+    assert np.allclose(got, Y[pi_out[rows]], rtol=1e-13, atol=1e-13)
+    ent = orc.product_entries(Wh, Xb, "bf16", pi_in, pi_out, rows, np.arange(24))
+    assert np.allclose(got, ent, rtol=1e-13, atol=1e-13)
+    # a swapped direction of pi_in (scatter instead of gather) must not pass
+    inv = np.argsort(pi_in)
+    assert not np.allclose(orc.product_rows(Wh[rows], Xb, "bf16", inv), Y[pi_out[rows]], rtol=1e-6, atol=1e-6)
+    # identity order and ReLU
+    Y0 = orc.product(Wh, Xb, "bf16", None, None, acc=np.float64, relu=True)
+    assert np.allclose(orc.product_rows(Wh[rows], Xb, "bf16", None, relu=True), Y0[rows], rtol=1e-13, atol=1e-13)
+
+
 def test_chain_equals_composition_and_identity_case():
     case = synth.small_case(64, 64, 16, 32, 12, "f16", 27)
     Wh1 = _packed(case)[4]
