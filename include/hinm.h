@@ -109,6 +109,22 @@ hinm_status hinm_pack(const hinm_shape* shape, const void* W,
                       void* vals, uint8_t* nm_idx, int32_t* vec_idx,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): hinm_pack with its score workspace in a
+ * device array that is part of the library image.  Same inputs, outputs, selection rules and
+ * results (bit for bit) as hinm_pack.  Limit: (M / V) * K <= HINM_PACK_STATIC_MAX_SCORES (one binary64
+ * score per tile and column, 4 MiB per GPU, held from the library's load until the process ends);
+ * larger layers return HINM_ERR_WORKSPACE before anything is launched.  The call allocates and
+ * frees nothing and records kernel launches only.  All calls on one GPU share the one array: two
+ * calls whose kernels may overlap there (different streams, no ordering between them) race and
+ * give unspecified packed arrays; calls on one stream, or ordered by events, are safe.  Nothing in
+ * the array has to be cleared between calls (every score that is read was written by the same
+ * call).  The first call on a device looks up the array's address and, like every entry point of
+ * this library, may set a kernel attribute: make one call per device outside stream capture first. */
+#define HINM_PACK_STATIC_MAX_SCORES 524288
+hinm_status hinm_pack_static(const hinm_shape* shape, const void* W,
+                             void* vals, uint8_t* nm_idx, int32_t* vec_idx, void* stream);
+
 /* Section 3.2 ("tile-wise input channel permutation"; the per-tile orders sigma_i^t of Section 4.2):
  * hinm_pack with a caller-given order of the kept column vectors.  tile_order is int32 [T][K] in
  * device memory, row t a permutation of the input channels 0..K-1; the surviving columns of tile t

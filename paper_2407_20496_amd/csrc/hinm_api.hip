@@ -59,6 +59,34 @@ hinm_status run_spmm(const SpmmArgs& a, uint32_t flags, hipStream_t stream) {
 
 size_t elem_bytes_out(uint32_t flags) { return (flags & HINM_OUT_F32) ? 4 : 2; }
 
+// ---- hinm_pack_static: the score workspace of the pack kernels in a file-scope device array -------------
+// One binary64 score per tile and column, at most kStaticScoreCount of them (4 MiB).  Every GPU the library runs
+// on holds its own copy of the array at its own address until the process ends.
+constexpr size_t kStaticScoreCount = (size_t)HINM_PACK_STATIC_MAX_SCORES;
+static __device__ __align__(256) double scratch[kStaticScoreCount];
+
+// In host code `scratch` is only a stand-in for the symbol: the device address comes from
+// hipGetSymbolAddress, once per device with that device current, and is kept per device.
+constexpr int kStaticMaxDevices = 64;
+hipError_t static_scores(double** out) {
+  static std::atomic<double*> per_device[kStaticMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kStaticMaxDevices) return hipErrorInvalidDevice;
+  double* p = per_device[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* addr = nullptr;
+    e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!addr) return hipErrorInvalidSymbol;
+    p = static_cast<double*>(addr);
+    per_device[dev].store(p, std::memory_order_release);  // two first calls racing store the same address
+  }
+  *out = p;
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -96,6 +124,22 @@ static hinm_status run_pack(const hinm_shape* shape, const void* W, const float*
 hinm_status hinm_pack(const hinm_shape* shape, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
                       void* workspace, size_t workspace_bytes, void* stream) {
   return run_pack(shape, W, nullptr, false, nullptr, vals, nm_idx, true, vec_idx, workspace, workspace_bytes, stream);
+}
+
+hinm_status hinm_pack_static(const hinm_shape* shape, const void* W, void* vals, uint8_t* nm_idx, int32_t* vec_idx,
+                             void* stream) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (!W || !vals || !nm_idx || !vec_idx) return HINM_ERR_NULL;
+  // the size limit comes before anything touches the device
+  if ((size_t)(shape->M / shape->V) * (size_t)shape->K > kStaticScoreCount) return HINM_ERR_WORKSPACE;
+  if (!aligned(vals, 8) || !aligned(vec_idx, 4) || !aligned(W, 2)) return HINM_ERR_SHAPE;
+  double* scores = nullptr;
+  if (static_scores(&scores) != hipSuccess) return HINM_ERR_DEVICE;
+  // every score the select step reads is written by the score step of the same call: nothing to clear
+  const PackArgs a{*shape, W, nullptr, nullptr, vals, nm_idx, vec_idx, scores};
+  hipError_t e = launch_pack(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 
 hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int32_t* tile_order, void* vals,

@@ -129,6 +129,20 @@ def test_null_and_workspace_errors_are_reported_before_any_launch():
     assert call(flags=0x300) == 5
 
 
+def test_pack_static_rejects_layers_beyond_its_array_before_touching_the_device():
+    lib = hinm.load_library()
+    fake = 0x1000
+    big = binding._Shape(16384, 16384, 128, 8192, 1)          # 128 tiles x 16384 columns: four times the array
+    assert lib.hinm_pack_static(C.byref(big), fake, fake, fake, fake, None) == 4
+    edge = binding._Shape(8192, 8200, 128, 4096, 1)           # 64 x 8200 scores: just beyond
+    assert lib.hinm_pack_static(C.byref(edge), fake, fake, fake, fake, None) == 4
+    ok_shape = binding._Shape(256, 256, 16, 128, 0)
+    assert lib.hinm_pack_static(C.byref(ok_shape), None, fake, fake, fake, None) == 1
+    assert lib.hinm_pack_static(C.byref(ok_shape), fake, fake + 2, fake, fake, None) == 2
+    text = open(os.path.join(ROOT, "include", "hinm.h")).read()
+    assert f"#define HINM_PACK_STATIC_MAX_SCORES {hinm.PACK_STATIC_MAX_SCORES}" in text
+
+
 def test_chain_validation():
     lib = hinm.load_library()
     fake = 0x1000
