@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the HiNM sparse-GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5]
 
 A step is one pass of the run-time path (gather through vector index o pi_in,
 sparse-MFMA product, pi_out scatter epilogue: hinm_spmm, or hinm_chain for c4)
@@ -15,9 +15,14 @@ Other workloads: `pack-c5[-ordered|-scored|-vectors]` (the offline compression s
 `sweep-resnet` (every layer of a model block at several vector sizes and vector sparsities, with and
 without channel orders, beside the dense GEMM).
 
+The default workload is the largest configuration, C5 (16384 x 16384 bf16, N = 8192); the same run then times
+every other configuration (C1, C2, the twelve C3 cases, the C4 chain) briefly and reports them under
+`per_config`.  `--workload calib` runs the calibration kernels (measured ceilings of the machine) alone.
+
 Prints ONE JSON line: metric / value / unit (dense-equivalent TFLOP/s of the whole job), ms_per_step, the
-workload in `config`, `roofline` (algorithmic bytes or stored-value flops per launch over the measured kernel
-time, against the HBM or MFMA peak) and `cpu_baseline` (the CPU oracle timed on a bounded sample).
+workload in `config`, `roofline` (algorithmic bytes or stored-value flops per launch over the average launch
+duration from HIP events over the timed region, against the nominal HBM or MFMA peak and against this run's
+calibration), `per_config`, `calibration` and `cpu_baseline` (the CPU oracle timed on a bounded sample).
 """
 from __future__ import annotations
 
@@ -63,14 +68,322 @@ def algorithmic_bytes(c, N, layers=1):
     return per_layer * layers
 
 
+def graph_replay_ms(torch, launch, steps):
+    """Captures `steps` calls of launch(i) into one HIP graph, replays it once untimed and once between two
+    HIP events recorded on the stream the replay is launched on; returns (wall ms, event ms) of the timed replay."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(steps):
+                launch(i)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    graph.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3, ev0.elapsed_time(ev1)
+
+
+def calibrate(torch, hinm, dev, dtype, quick=True):
+    """Ceilings of this machine measured with the plain kernels of include/hinm_calib.h, each between two HIP
+    events: streaming copy / fill / read over 1 GiB (beyond the 256 MB memory-side cache), the issue rate of the
+    32x32x32 sparse matrix instruction from registers, the cost of an empty graph node."""
+    out = {}
+    nbytes = 1 << 30
+    a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    b = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(2048 * 256, dtype=torch.float32, device=dev)
+    a.fill_(1)
+    b.fill_(2)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    reps = 5 if quick else 20
+    for nt in (False, True):
+        tag = "_nt" if nt else ""
+        ms = timed(lambda: hinm.hinm_calib_copy(a, b, nbytes, nt), reps)
+        out["copy" + tag + "_gbps"] = round(2 * nbytes / ms / 1e6, 1)       # bytes read + bytes written
+        ms = timed(lambda: hinm.hinm_calib_fill(b, nbytes, nt), reps)
+        out["write" + tag + "_gbps"] = round(nbytes / ms / 1e6, 1)
+        ms = timed(lambda: hinm.hinm_calib_read(a, nbytes, sink, nt), reps)
+        out["read" + tag + "_gbps"] = round(nbytes / ms / 1e6, 1)
+    iters = 4000
+    flops = [0.0]
+
+    def smf():
+        flops[0] = hinm.hinm_calib_smfmac(dtype, iters, sink)
+    ms = timed(smf, reps)
+    out["smfmac_stored_tflops"] = round(flops[0] / ms / 1e9, 1)                # hardware rating counts twice this
+    out["smfmac_kernel_ms"] = round(ms, 4)
+    nodes = 1000
+    _, ev_ms = graph_replay_ms(torch, lambda i: hinm.hinm_calib_empty(), nodes)
+    out["graph_node_floor_us"] = round(ev_ms * 1e3 / nodes, 3)
+    if not quick:
+        # a compute unit drawing L2-resident data into LDS (2 MB region shared by all workgroups)
+        region = 2 << 20
+        passes = 64
+        ms = timed(lambda: hinm.hinm_calib_lds_stream(a, region, passes, 256), reps)
+        out["l2_to_lds_gbps_256_workgroups"] = round(256 * passes * region / ms / 1e6, 1)
+        ms = timed(lambda: hinm.hinm_calib_lds_stream(a, region, passes, 512), reps)
+        out["l2_to_lds_gbps_512_workgroups"] = round(512 * passes * region / ms / 1e6, 1)
+        # store-only passes shaped like the C2 output (3072 x 4096 fp16): natural and permuted rows, three piece sizes
+        M, N = 3072, 4096
+        Ys = [torch.empty((M, N), dtype=torch.int16, device=dev) for _ in range(24)]    # 600 MB rotated
+        rows = torch.from_numpy(np.random.default_rng(20496).permutation(M).astype(np.int32)).to(dev)
+        for piece in (64, 128, 256, 512):
+            for label, r in (("natural", None), ("permuted", rows)):
+                _, ev_ms = graph_replay_ms(
+                    torch, lambda i: hinm.hinm_calib_scatter_rows(Ys[i % len(Ys)], M, N, N, r, piece), 240)
+                out[f"c2_output_store_only_us_{piece}B_{label}"] = round(ev_ms * 1e3 / 240, 2)
+        del Ys
+    del a, b
+    torch.cuda.empty_cache()
+    return out
+
+
+class CaseRun:
+    """One workload resident in HBM: packed (and prepared) on the GPU, enough rotated copies to exceed the
+    memory-side cache, and the launch closure that bench times."""
+
+    def __init__(self, key, c, args, torch, hinm, dev, keep_dense=False, columns=0):
+        self.key, self.torch, self.hinm = key, torch, hinm
+        if columns:
+            import dataclasses
+            c = dataclasses.replace(c, N=columns, name=f"{c.name} at N = {columns}")
+        self.c = c
+        self.chain = key == "c4"
+        N = self.N = c.N
+        self.n_layers = 2 if self.chain else 1
+        self.variant = args.variant
+        self.use_prepared = (not args.canonical) and c.V % 32 == 0
+
+        def dev_bits(a):
+            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev)
+
+        vb, nb, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+        packed = []
+        self.W_dense = None
+        for l in range(self.n_layers):
+            W = dev_bits(c.weights(l))
+            vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
+            nm = torch.empty(nb, dtype=torch.uint8, device=dev)
+            vec = torch.empty(cb // 4, dtype=torch.int32, device=dev)
+            ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
+            hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
+            torch.cuda.synchronize()
+            del ws
+            pin = None if args.identity else torch.from_numpy(c.pi_in(l)).to(dev)
+            pout = None if args.identity else torch.from_numpy(c.pi_out(l)).to(dev)
+            prep = None
+            if self.use_prepared:
+                pbytes = hinm.hinm_prepare_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
+                prep = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+                hinm.hinm_prepare(c.M, c.K, c.V, c.Kv, c.dtype, vals, nm, vec, pin, pout, prep, pbytes)
+                torch.cuda.synchronize()
+            if l == 0 and keep_dense:
+                self.W_dense = W
+            del W
+            packed.append((vals, nm, vec, pin, pout, prep))
+        ldn = self.ldn = N if N == 1 else (N + 7) // 8 * 8 + args.ld_pad
+        Xh = np.zeros((c.K, ldn), dtype=np.uint16)
+        Xh[:, :N] = c.activations()
+        self.X0 = dev_bits(Xh)
+        per_set = sum(t.numel() * t.element_size() for (v, n, ve, _, _, _) in packed for t in (v, n, ve)) \
+            + (c.K + c.M) * ldn * 2 * self.n_layers
+        self.n_sets = n_sets = args.sets if args.sets else max(2, min(64, int(np.ceil(600e6 / per_set))))
+        self.sets = []
+        for i in range(n_sets):
+            layers = []
+            for (vals, nm, vec, pin, pout, prep) in packed:
+                if self.use_prepared:
+                    layers.append((None, None, None, None, None, prep if i == 0 else prep.clone()))
+                elif i == 0:
+                    layers.append((vals, nm, vec, pin, pout, None))
+                else:
+                    layers.append((vals.clone(), nm.clone(), vec.clone(), pin, pout, None))
+            X = self.X0 if i == 0 else self.X0.clone()
+            Y = torch.zeros((c.M, ldn), dtype=torch.int16, device=dev)
+            scratch = torch.empty(c.M * ldn * 2, dtype=torch.uint8, device=dev) if self.chain else None
+            self.sets.append((layers, X, Y, scratch))
+        self.ws_bytes = hinm.hinm_spmm_prepared_workspace(c.M, c.K, c.V, c.Kv, c.dtype, N) if self.use_prepared else 0
+        self.ws = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=dev) if self.ws_bytes else None
+        self.bytes_step = algorithmic_bytes(c, N, self.n_layers)
+        self.flops_dense_equiv = 2.0 * c.M * c.K * N * self.n_layers
+        self.flops_stored = 2.0 * c.M * (c.Kv // 2) * N * self.n_layers
+        # which kernels one step launches: asked of the library (a dry run of its dispatch), not re-derived here
+        if self.use_prepared:
+            text, n = hinm.hinm_spmm_prepared_plan(c.M, c.K, c.V, c.Kv, c.dtype, N, ldn, ldn, self.variant << 16)
+            self.kernels, self.kernel_launches_per_step = text, n * self.n_layers
+        else:
+            self.kernels = "hinm_spmm on the canonical arrays (kernel chosen by the library)"
+            self.kernel_launches_per_step = self.n_layers
+        # a layer whose tiles are split over two kernel launches (whole rounds + remainder) is still one product:
+        # bytes and flops are priced per layer, over the time of the layer's launches together
+        self.launches_per_step = self.n_layers
+
+    def step(self, i):
+        hinm, c, N, ldn = self.hinm, self.c, self.N, self.ldn
+        layers, X, Y, scratch = self.sets[i % self.n_sets]
+        vflag = self.variant << 16
+        if self.chain:
+            ls = [hinm.Layer(c.M, c.K, c.V, c.Kv, c.dtype, v, n, ve, pi, po,
+                             (hinm.EPI_RELU if l == 0 else 0) | (vflag if pr is not None else 0), pr)
+                  for l, (v, n, ve, pi, po, pr) in enumerate(layers)]
+            hinm.hinm_chain(ls, N, X, ldn, Y, ldn, scratch, scratch.numel())
+        else:
+            v, n, ve, pi, po, pr = layers[0]
+            if pr is not None:
+                hinm.hinm_spmm_prepared(c.M, c.K, c.V, c.Kv, c.dtype, N, pr, X, ldn, Y, ldn, vflag, self.ws, self.ws_bytes)
+            else:
+                hinm.hinm_spmm(c.M, c.K, c.V, c.Kv, c.dtype, N, v, n, ve, pi, po, X, ldn, Y, ldn, 0)
+
+    def estimate_step_s(self):
+        torch = self.torch
+        self.step(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(3):
+            self.step(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / 3
+
+    def time_steps(self, steps, warmup, graph=True):
+        """(wall ms per step, HIP-event ms per step) over exactly `steps` timed steps after `warmup` untimed ones."""
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        if graph:
+            wall, ev = graph_replay_ms(torch, self.step, steps)
+        else:
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            ev0.record()
+            for i in range(steps):
+                self.step(i)
+            ev1.record()
+            torch.cuda.synchronize()
+            wall, ev = (time.perf_counter() - t0) * 1e3, ev0.elapsed_time(ev1)
+        return wall / steps, ev / steps
+
+    def roofline(self, launch_ms, calib):
+        """The dominant kernel against the roofline that bounds it: algorithmic bytes (or stored-value flops) of one
+        launch over the average launch duration measured with HIP events over the timed region."""
+        n = self.n_layers
+        mem_bound = (self.bytes_step / HBM_PEAK_GBPS / 1e9) >= (self.flops_stored / MFMA_DENSE_PEAK_TFLOPS / 1e12)
+        if mem_bound:
+            ach = self.bytes_step / n / (launch_ms * 1e-3) / 1e9
+            r = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                 "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None}
+            if calib:
+                r["peak_calibrated"] = calib["copy_gbps"]
+                r["frac_calibrated"] = round(ach / calib["copy_gbps"], 4)
+                r["peak_calibrated_is"] = "1 GiB device copy kernel, bytes read + written per second"
+        else:
+            ach = self.flops_stored / n / (launch_ms * 1e-3) / 1e12
+            r = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
+                 "frac": round(ach / MFMA_DENSE_PEAK_TFLOPS, 4), "traffic": None}
+            if calib:
+                r["peak_calibrated"] = calib["smfmac_stored_tflops"]
+                r["frac_calibrated"] = round(ach / calib["smfmac_stored_tflops"], 4)
+                r["peak_calibrated_is"] = "register-resident 32x32x32 sparse-MFMA loop, stored-value flops per second"
+        r["kernel"] = self.kernels
+        r["layers_per_step"] = self.n_layers
+        r["kernel_launches_per_step"] = self.kernel_launches_per_step
+        if calib and mem_bound:
+            r["frac_of_read_stream"] = round(ach / calib["read_gbps"], 4)
+        r["avg_layer_ms_hip_events_over_timed_region"] = round(launch_ms, 6)
+        r["algorithmic_bytes_per_launch"] = self.bytes_step // n
+        r["stored_value_flops_per_launch"] = self.flops_stored / n
+        return r
+
+    def free(self):
+        self.sets = None
+        self.X0 = self.W_dense = self.ws = None
+        self.torch.cuda.empty_cache()
+
+
+def stored_traffic(key, canonical):
+    """HBM bytes per launch from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            tr = json.load(f).get(key if not canonical else key + "-canonical")
+        if tr:
+            return tr["fetch_bytes"] + tr["write_bytes"], "stored summary, not measured in this run: " + tr.get("source", "")
+    except (OSError, ValueError):
+        pass
+    return None, None
+
+
+def measure_traffic_live(key, extra_args):
+    """HBM bytes per launch of the workload's SpMM kernels from two rocprofv3 --pmc runs (FETCH_SIZE, then
+    WRITE_SIZE) of this script as child processes, each scaled by what the same counter reads for the 256 MiB
+    bitwise_not probe of known size in the same run.  Must run before this process touches the GPU."""
+    import csv
+    import glob
+    import subprocess
+    import tempfile
+    totals, factors = {}, {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        out = tempfile.mkdtemp(prefix="hinm_pmc_", dir="/tmp")
+        cmd = ["rocprofv3", "--pmc", counter, "--output-format", "csv", "-d", out, "-o", "p", "--",
+               "python3", os.path.abspath(__file__), "--workload", key, "--no-cpu", "--no-dense", "--no-graph",
+               "--no-per-config", "--no-calib", "--steps", "4", "--warmup", "1", "--copy-probe"] + extra_args
+        env = dict(os.environ, TMPDIR="/tmp")
+        res = subprocess.run(cmd, cwd="/tmp", env=env, capture_output=True, text=True, timeout=300)
+        files = glob.glob(os.path.join(out, "**", "*counter_collection.csv"), recursive=True)
+        if res.returncode != 0 or not files:
+            return None, f"rocprofv3 --pmc {counter} failed (rc {res.returncode})"
+        spmm, probe = {}, []
+        with open(files[0]) as f:
+            for r in csv.DictReader(f):
+                if r["Counter_Name"] != counter:
+                    continue
+                k, v = r["Kernel_Name"], float(r["Counter_Value"])
+                if "spmm_" in k:
+                    spmm.setdefault(k, []).append(v)
+                elif "bitwise_not" in k:
+                    probe.append(v)
+        if not spmm or not probe:
+            return None, "no SpMM or probe dispatches in the counter output"
+        factors[counter] = 262144.0 / (sum(probe) / len(probe))
+        # one launch of each kernel per step (a step of two different kernels adds them)
+        totals[counter] = sum(sum(v) / len(v) for v in spmm.values()) * 1024.0 * factors[counter]
+    return int(totals["FETCH_SIZE"] + totals["WRITE_SIZE"]), (
+        f"measured in this run: rocprofv3 --pmc FETCH_SIZE (x{factors['FETCH_SIZE']:.2f}) and WRITE_SIZE "
+        f"(x{factors['WRITE_SIZE']:.2f}) on child runs, read {totals['FETCH_SIZE'] / 1e6:.1f} MB + written "
+        f"{totals['WRITE_SIZE'] / 1e6:.1f} MB per launch")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c5")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the same-shape dense GEMM reference")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the short runs of the other configurations that fill `per_config`")
+    ap.add_argument("--no-calib", action="store_true", help="skip the calibration kernels (measured peaks)")
+    ap.add_argument("--measure-traffic", action="store_true",
+                    help="measure roofline.traffic in this run with two rocprofv3 --pmc child runs instead of "
+                         "reading the committed summary")
     ap.add_argument("--identity", action="store_true", help="run with identity permutations")
     ap.add_argument("--canonical", action="store_true",
                     help="call hinm_spmm on the canonical arrays instead of hinm_spmm_prepared")
@@ -92,6 +405,15 @@ def main():
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    live_traffic = None
+    if args.measure_traffic and args.workload in workloads():
+        extra = (["--identity"] if args.identity else []) + (["--canonical"] if args.canonical else []) \
+            + (["--variant", str(args.variant)] if args.variant else [])
+        try:
+            live_traffic = measure_traffic_live(args.workload, extra)
+        except Exception as err:  # the headline run goes on without it
+            live_traffic = (None, f"live traffic measurement failed: {err!r}")
+
     import torch
     import paper_2407_20496_amd as hinm
     hinm.load_library()  # fails loudly if the HIP library is not built
@@ -101,6 +423,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.workload == "calib":
+        return bench_calib(args, torch, hinm, dev)
     if args.workload in PACK_WORKLOADS:
         return bench_pack(args, torch, hinm, dev)
     if args.workload in SWEEP_WORKLOADS:
@@ -113,180 +437,33 @@ def main():
     if args.workload.startswith("vectors-") and args.workload[8:] in wl:
         return bench_vectors(args, torch, hinm, dev, wl[args.workload[8:]])
     if args.workload not in wl:
-        print("unknown workload; choose from: " + " ".join(PACK_WORKLOADS + SWEEP_WORKLOADS + ICP_WORKLOADS + OCP_WORKLOADS) + " "
+        print("unknown workload; choose from: calib " + " ".join(PACK_WORKLOADS + SWEEP_WORKLOADS + ICP_WORKLOADS + OCP_WORKLOADS) + " "
               + " ".join(wl)
               + " vectors-<any of the latter>", file=sys.stderr)
         sys.exit(2)
-    c = wl[args.workload]
-    if args.columns:   # the same layer at another number of columns (batched decode: 32 .. 512)
-        import dataclasses
-        c = dataclasses.replace(c, N=args.columns, name=f"{c.name} at N = {args.columns}")
-    chain = args.workload == "c4"
-    N = c.N
-    n_layers = 2 if chain else 1
 
-    def dev_bits(a):
-        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev)
+    run = CaseRun(args.workload, wl[args.workload], args, torch, hinm, dev, keep_dense=not args.no_dense,
+                  columns=args.columns)
+    c, N, n_layers, chain = run.c, run.N, run.n_layers, run.chain
+    calib = None if args.no_calib else calibrate(torch, hinm, dev, c.dtype)
 
-    use_prepared = (not args.canonical) and c.V % 32 == 0
-    # ---- inputs: drawn on the host from the seeded generator, packed (and prepared) on the GPU ----
-    vb, nb, cb, wb = hinm.hinm_pack_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
-    packed = []
-    for l in range(n_layers):
-        W = dev_bits(c.weights(l))
-        vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
-        nm = torch.empty(nb, dtype=torch.uint8, device=dev)
-        vec = torch.empty(cb // 4, dtype=torch.int32, device=dev)
-        ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
-        hinm.hinm_pack(c.M, c.K, c.V, c.Kv, c.dtype, W, vals, nm, vec, ws, wb)
-        torch.cuda.synchronize()
-        del ws
-        pin = None if args.identity else torch.from_numpy(c.pi_in(l)).to(dev)
-        pout = None if args.identity else torch.from_numpy(c.pi_out(l)).to(dev)
-        prep = None
-        if use_prepared:
-            pbytes = hinm.hinm_prepare_sizes(c.M, c.K, c.V, c.Kv, c.dtype)
-            prep = torch.empty(pbytes, dtype=torch.uint8, device=dev)
-            hinm.hinm_prepare(c.M, c.K, c.V, c.Kv, c.dtype, vals, nm, vec, pin, pout, prep, pbytes)
-            torch.cuda.synchronize()
-        packed.append((W if (l == 0 and not args.no_dense) else None, vals, nm, vec, pin, pout, prep))
-        if not (l == 0 and not args.no_dense):
-            del W
-    ldn = N if N == 1 else (N + 7) // 8 * 8 + args.ld_pad
-    Xh = np.zeros((c.K, ldn), dtype=np.uint16)
-    Xh[:, :N] = c.activations()
-    X0 = dev_bits(Xh)
+    est = run.estimate_step_s()
+    steps = args.steps if args.steps is not None else int(min(5000, max(20, 1.0 / max(est, 1e-6))))
+    warmup = args.warmup if args.warmup is not None else max(3, steps // 10)
+    # The K timed steps are captured once into a HIP graph and replayed: a step of the small configurations lasts
+    # a few microseconds, less than a host-side launch through Python, so launching from the host would time the
+    # interpreter.  The graph holds exactly K steps (kernel_launches_per_step kernel nodes each).
+    ms_per_step, gpu_ms_per_step = run.time_steps(steps, warmup, graph=not args.no_graph)
+    launch_ms = gpu_ms_per_step / run.launches_per_step
 
-    bytes_step = algorithmic_bytes(c, N, n_layers)
-    per_set = sum(t.numel() * t.element_size() for (_, v, n, ve, _, _, _) in packed for t in (v, n, ve)) \
-        + (c.K + c.M) * ldn * 2 * n_layers
-    n_sets = args.sets if args.sets else max(2, min(64, int(np.ceil(600e6 / per_set))))
-    sets = []
-    for i in range(n_sets):
-        layers = []
-        for (_, vals, nm, vec, pin, pout, prep) in packed:
-            if use_prepared:
-                layers.append((None, None, None, None, None, prep if i == 0 else prep.clone()))
-            elif i == 0:
-                layers.append((vals, nm, vec, pin, pout, None))
-            else:
-                layers.append((vals.clone(), nm.clone(), vec.clone(), pin, pout, None))
-        X = X0 if i == 0 else X0.clone()
-        Y = torch.zeros((c.M, ldn), dtype=torch.int16, device=dev)
-        scratch = torch.empty(c.M * ldn * 2, dtype=torch.uint8, device=dev) if chain else None
-        sets.append((layers, X, Y, scratch))
-
-    ws_bytes = hinm.hinm_spmm_prepared_workspace(c.M, c.K, c.V, c.Kv, c.dtype, N) if use_prepared else 0
-    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
-
-    def step(i):
-        layers, X, Y, scratch = sets[i % n_sets]
-        vflag = args.variant << 16
-        if chain:
-            ls = [hinm.Layer(c.M, c.K, c.V, c.Kv, c.dtype, v, n, ve, pi, po,
-                             (hinm.EPI_RELU if l == 0 else 0) | (vflag if pr is not None else 0), pr)
-                  for l, (v, n, ve, pi, po, pr) in enumerate(layers)]
-            hinm.hinm_chain(ls, N, X, ldn, Y, ldn, scratch, scratch.numel())
+    roofline = run.roofline(launch_ms, calib)
+    if not args.columns:
+        if live_traffic is not None:
+            roofline["traffic"], roofline["traffic_source"] = live_traffic
         else:
-            v, n, ve, pi, po, pr = layers[0]
-            if pr is not None:
-                hinm.hinm_spmm_prepared(c.M, c.K, c.V, c.Kv, c.dtype, N, pr, X, ldn, Y, ldn, vflag, ws, ws_bytes)
-            else:
-                hinm.hinm_spmm(c.M, c.K, c.V, c.Kv, c.dtype, N, v, n, ve, pi, po, X, ldn, Y, ldn, 0)
-
-    flops_dense_equiv = 2.0 * c.M * c.K * N * n_layers
-    flops_stored = 2.0 * c.M * (c.Kv // 2) * N * n_layers
-    # pick K so the timed region is long enough to be meaningful but well under a minute
-    step(0)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(3):
-        step(i)
-    torch.cuda.synchronize()
-    est = (time.perf_counter() - t0) / 3
-    steps = args.steps if args.steps is not None else int(min(5000, max(50, 1.0 / max(est, 1e-6))))
-    warmup = args.warmup if args.warmup is not None else max(5, steps // 10)
-
-    for i in range(warmup):
-        step(i)
-    torch.cuda.synchronize()
-    # The K timed steps are captured once into a HIP graph and replayed: a step lasts a few
-    # microseconds, less than a host-side launch through Python, so launching from the host would
-    # time the interpreter.  The graph holds exactly K kernel launches (2K for the chain).
-    graph = None
-    if not args.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(steps):
-                    step(i)
-        torch.cuda.current_stream().wait_stream(side)
-        graph.replay()          # untimed replay (also part of warm-up)
-        torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    if graph is not None:
-        graph.replay()
-    else:
-        for i in range(steps):
-            step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / steps
-    gpu_ms_per_step = ev0.elapsed_time(ev1) / steps
-
-    # ---- per-launch kernel time with HIP events on the launch stream (same rotation) ----------
-    n_ev = min(steps, 200)
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
-    for i, (a, b) in enumerate(pairs):
-        a.record()
-        step(i)
-        b.record()
-    torch.cuda.synchronize()
-    per_launch_ms = sorted(a.elapsed_time(b) for a, b in pairs)
-    kernel_ms_avg = float(np.mean(per_launch_ms)) / n_layers
-    kernel_ms_med = float(per_launch_ms[len(per_launch_ms) // 2]) / n_layers
-    # the back-to-back rate bounds the kernel time from above as well; use the smaller of the two
-    kernel_ms = min(kernel_ms_avg, gpu_ms_per_step / n_layers)
-
-    mem_bound = (bytes_step / HBM_PEAK_GBPS / 1e9) >= (flops_stored / MFMA_DENSE_PEAK_TFLOPS / 1e12)
-    if mem_bound:
-        ach = bytes_step / n_layers / (kernel_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None}
-    else:
-        ach = flops_stored / n_layers / (kernel_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / MFMA_DENSE_PEAK_TFLOPS, 4), "traffic": None}
-    if use_prepared:
-        k8 = (c.K + 7) // 8 * 8
-        panel_fits = (k8 + 8) * 128 + 8 * 32 * 144 <= 160 * 1024
-        roofline["kernel"] = ("spmm_rows16_prepared_kernel" if (N <= 16 and args.variant in (0, 11)) else
-                              "spmm_skinny_prepared_kernel" if N <= 32 else
-                              "spmm_panel_prepared_kernel" if (panel_fits and args.variant in (0, 15)) else
-                              "spmm_tile_prepared_kernel")
-    else:
-        roofline["kernel"] = ("spmm_skinny_kernel" if N <= 16 or c.V % 32 else
-                              "spmm_tile_dma_kernel" if c.Kv % 64 == 0 else "spmm_tile_kernel")
-    if args.columns:   # not one of the profiled configurations: the library picks the kernel by shape
-        roofline["kernel"] = None
-    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
-    try:
-        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
-            tr = json.load(f).get(args.workload if not args.canonical else args.workload + "-canonical")
-        if tr and mem_bound and not args.columns:
-            roofline["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
-            roofline["traffic_source"] = tr.get("source")
-    except (OSError, ValueError):
-        pass
-    roofline["kernel_ms_avg"] = round(kernel_ms, 6)
-    roofline["kernel_ms_median_event_pair"] = round(kernel_ms_med, 6)
-    roofline["algorithmic_bytes_per_launch"] = bytes_step // n_layers
-    roofline["stored_value_flops_per_launch"] = flops_stored / n_layers
+            roofline["traffic"], roofline["traffic_source"] = stored_traffic(args.workload, args.canonical)
+        if roofline["traffic"]:
+            roofline["traffic_over_algorithmic"] = round(roofline["traffic"] / (run.bytes_step / n_layers), 2)
 
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -298,10 +475,10 @@ def main():
 
     # ---- same-shape dense GEMM (library) on the same tensors, same timing method ---------------
     dense = None
-    if not args.no_dense and packed[0][0] is not None:
+    if run.W_dense is not None:
         tdt = torch.float16 if c.dtype == "f16" else torch.bfloat16
-        Wd = packed[0][0].view(tdt).reshape(c.M, c.K)
-        Xd = X0.view(tdt).reshape(c.K, ldn)[:, :N].contiguous()
+        Wd = run.W_dense.view(tdt).reshape(c.M, c.K)
+        Xd = run.X0.view(tdt).reshape(c.K, run.ldn)[:, :N].contiguous()
         for _ in range(3):
             torch.matmul(Wd, Xd)
         torch.cuda.synchronize()
@@ -315,13 +492,9 @@ def main():
         dms = e0.elapsed_time(e1) / reps
         dense = {"ms": round(dms, 5), "tflops": round(2.0 * c.M * c.K * N / dms / 1e9, 2),
                  "note": "torch.matmul on the unpruned W, single buffer set (cache-warm)"}
+        del Wd, Xd
 
-    # ---- CPU oracle baseline on the host cores ---------------------------------------------------
-    cpu = None
-    if not args.no_cpu:
-        cpu = cpu_baseline(c, N, chain)
-
-    value = flops_dense_equiv / (ms_per_step * 1e-3) / 1e12
+    value = run.flops_dense_equiv / (ms_per_step * 1e-3) / 1e12
     out = {
         "metric": "hinm_spmm_dense_equiv_tflops", "value": round(value, 3), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
@@ -330,53 +503,118 @@ def main():
         "config": {"workload": c.name + (" (two-layer chain)" if chain else ""), "M": c.M, "K": c.K, "V": c.V,
                    "Kv": c.Kv, "N": N, "layers": n_layers,
                    "permutation": "identity" if args.identity else "seeded random pi_in/pi_out",
-                   "buffer_sets_rotated": n_sets,
+                   "buffer_sets_rotated": run.n_sets,
                    "entry_point": ("hinm_chain" if chain else "hinm_spmm")
-                   + ("_prepared" if use_prepared and not chain else "") + (" (prepared layers)" if chain and use_prepared else ""),
+                   + ("_prepared" if run.use_prepared and not chain else "") + (" (prepared layers)" if chain and run.use_prepared else ""),
                    "variant": args.variant,
-                   "launch": "host loop" if graph is None else "one HIP graph of K steps"},
+                   "launch": "host loop" if args.no_graph else "one HIP graph of K steps"},
         "gpu_ms_per_step_events": round(gpu_ms_per_step, 6),
-        "hbm_gbps_algorithmic": round(bytes_step / (gpu_ms_per_step * 1e-3) / 1e9, 1),
-        "stored_value_tflops": round(flops_stored / (gpu_ms_per_step * 1e-3) / 1e12, 3),
-        "roofline": roofline, "cpu_baseline": cpu, "dense_gemm": dense,
+        "hbm_gbps_algorithmic": round(run.bytes_step / (gpu_ms_per_step * 1e-3) / 1e9, 1),
+        "stored_value_tflops": round(run.flops_stored / (gpu_ms_per_step * 1e-3) / 1e12, 3),
+        "roofline": roofline, "cpu_baseline": None, "dense_gemm": dense, "calibration": calib,
     }
+    run.free()
+
+    # ---- the other configurations, one short graph-timed run each -------------------------------
+    if not args.no_per_config and not args.columns:
+        per = {args.workload: {"us_per_step": round(gpu_ms_per_step * 1e3, 2), "bound": roofline["bound"],
+                               "frac": roofline["frac"], "frac_calibrated": roofline.get("frac_calibrated"),
+                               "kernel": roofline["kernel"], "layers_per_step": run.n_layers}}
+        for key, cc in wl.items():
+            if key == args.workload or key == "c5":
+                continue
+            try:
+                r = CaseRun(key, cc, args, torch, hinm, dev)
+                e = r.estimate_step_s()
+                k = int(min(2000, max(20, 0.25 / max(e, 1e-6))))
+                _, g_ms = r.time_steps(k, max(3, k // 10))
+                rf = r.roofline(g_ms / r.launches_per_step, calib)
+                per[key] = {"us_per_step": round(g_ms * 1e3, 2), "steps": k, "bound": rf["bound"],
+                            "achieved": rf["achieved"], "unit": rf["unit"], "frac": rf["frac"],
+                            "frac_calibrated": rf.get("frac_calibrated"), "kernel": rf["kernel"],
+                            "layers_per_step": r.n_layers,
+                            "dense_equiv_tflops": round(r.flops_dense_equiv / (g_ms * 1e-3) / 1e12, 1)}
+                r.free()
+                del r
+            except Exception as err:   # one configuration failing must not lose the headline
+                per[key] = {"error": repr(err)}
+        out["per_config"] = per
+        out["per_config_note"] = ("every BASELINE configuration timed in this run: HIP-event time of one graph replay / "
+                                  "steps; frac against the nominal peak of the bound (8 TB/s HBM or 2.5 PFLOP/s dense "
+                                  "fp16/bf16 on stored-value flops), frac_calibrated against this run's calibration; C1 is "
+                                  "launch-bound (no roofline claim)")
+
+    # ---- CPU oracle baseline on the host cores ---------------------------------------------------
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(c, N, chain)
     print(json.dumps(out))
 
 
+def bench_calib(args, torch, hinm, dev):
+    """The calibration kernels alone, long form: one JSON line with the measured ceilings."""
+    cal = calibrate(torch, hinm, dev, "bf16", quick=False)
+    cal16 = calibrate(torch, hinm, dev, "f16", quick=True)
+    cal["smfmac_stored_tflops_f16"] = cal16["smfmac_stored_tflops"]
+    print(json.dumps({"metric": "calibration", "value": cal["copy_gbps"], "unit": "GB/s", "n_gpus": 1, "steps": 20,
+                      "warmup": 1, "ms_per_step": None, "higher_is_better": True, "scaling": "weak",
+                      "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "calibration kernels (include/hinm_calib.h)"},
+                      "calibration": cal, "roofline": None, "cpu_baseline": None}))
+
+
 def cpu_baseline(c, N, chain):
-    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload."""
+    """The oracle as it stands (explicit masks, explicit permutation matrices, float32 matmul), timed on this
+    box's host cores on a bounded sample of the workload: two whole tiles plus rows spread over all tiles
+    (at most 1280 rows of W in all), all K input channels, and as many columns of X as keep the work near
+    2 TFLOP of float32 matmul."""
     from oracle import hinm_oracle as orc
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    # bounded sample: at most 8 tiles of W (all their rows) and at most 512 columns of X
-    tiles = min(c.T, 8)
-    rows = tiles * c.V
-    n = min(N, 512)
-    Wb = c.weights()[:rows]
+    rng = np.random.default_rng(20496)
+    whole = sorted(set([0, c.T // 2]))
+    extra_per_tile = max(1, min(8, (1280 - len(whole) * c.V) // max(1, c.T)))
+    Wb = c.weights()
+    rows = []
     t0 = time.perf_counter()
-    vals, nm, vec = orc.pack(Wb, c.dtype, c.V, c.Kv)
+    packed_tiles = {}
+    for t in range(c.T):
+        pick = np.arange(c.V) if t in whole else np.sort(rng.choice(c.V, min(c.V, extra_per_tile), replace=False))
+        rows.extend(t * c.V + pick)
+    rows = np.array(rows[:1280]) if len(rows) > 1280 else np.array(rows)
+    tiles = sorted(set((rows // c.V).tolist()))
+    Wh_rows = np.zeros((len(rows), c.K), dtype=np.uint16)
+    for t in tiles:
+        sl = slice(t * c.V, (t + 1) * c.V)
+        ov, on, oc = orc.pack(Wb[sl], c.dtype, c.V, c.Kv)
+        Wh_t = orc.unpack_fast(ov, on, oc, c.V, c.K, c.V)
+        sel = (rows // c.V) == t
+        Wh_rows[sel] = Wh_t[rows[sel] - t * c.V]
     t_pack = time.perf_counter() - t0
-    Wh = orc.unpack_fast(vals, nm, vec, rows, c.K, c.V)
+    del Wb
+    # columns: the permutation product P_in X dominates (2 K^2 n flops); keep the whole sample near 2 TFLOP
+    per_col = 2.0 * c.K * c.K + 2.0 * len(rows) * c.K + 2.0 * len(rows) * len(rows)
+    n = int(max(1, min(N, 2e12 // per_col)))
     Xb = c.activations()[:, :n]
     pin = c.pi_in()
-    pout = np.argsort(np.argsort(c.pi_out()[:rows])).astype(np.int32)   # a permutation of the sampled rows
+    pout = np.argsort(np.argsort(c.pi_out()[rows])).astype(np.int32)   # the sampled rows' own output order
     reps, t_prod = 0, 0.0
-    while t_prod < 5.0 and reps < 50:
+    while t_prod < 8.0 and reps < 20:
         t0 = time.perf_counter()
-        orc.spmm(Wh, Xb, c.dtype, pin, pout)
+        orc.spmm(Wh_rows, Xb, c.dtype, pin, pout)
         t_prod += time.perf_counter() - t0
         reps += 1
     t_one = t_prod / reps
     layers = 2 if chain else 1
-    return {"value": round(2.0 * rows * c.K * n / t_one / 1e12, 5), "unit": "TFLOP/s", "cores": int(threads),
+    return {"value": round(2.0 * len(rows) * c.K * n / t_one / 1e12, 5), "unit": "TFLOP/s", "cores": int(threads),
             "kind": "oracle",
-            "sample": f"oracle product (explicit permutation matrices, float32 numpy matmul) on {tiles} of {c.T} "
-                      f"tiles x {n} of {N} columns, {reps} repetitions, {t_one * 1e3:.1f} ms each; "
-                      f"oracle pack of those tiles {t_pack * 1e3:.1f} ms; host cpu_count {os.cpu_count()}"
-                      + ("; one layer of the two" if layers == 2 else "")}
+            "sample": f"oracle product (explicit permutation matrices, float32 numpy matmul) on {len(rows)} rows of W "
+                      f"(tiles {whole} whole, {extra_per_tile} rows of each other tile: {len(tiles)} of {c.T} tiles) x "
+                      f"{n} of {N} columns, {reps} repetitions, {t_one * 1e3:.1f} ms each; dense-equivalent flops of "
+                      f"the sample over that time; oracle pack of the {len(tiles)} tiles {t_pack * 1e3:.0f} ms; "
+                      f"host cpu_count {os.cpu_count()}" + ("; one layer of the two" if layers == 2 else "")}
 
 
 def bench_pack(args, torch, hinm, dev):

@@ -51,6 +51,14 @@
  *     HINM_ERR_DEVICE reports a failed launch.  W must be finite.
  *   - Alignment: vals, X and Y base pointers 16-byte aligned; ldx, ldy
  *     multiples of 8 elements unless N == 1 (then any ld >= 1).
+ *   - Readable extent of X: the kernels load X in 16-byte pieces, so for N > 1 every row is read up to
+ *     column 8 * ceil(N / 8) - 1, the last row included: X must be readable for
+ *     (K - 1) * ldx + 8 * ceil(N / 8) elements (ldx >= that rounded N guarantees it for an allocation of
+ *     K * ldx elements).  What those extra columns hold never reaches a result.
+ *   - HIP stream capture: the library records kernel launches only (no memset, copy, allocation or
+ *     synchronisation).  The first launch of a kernel on a device may raise that kernel's dynamic-LDS
+ *     limit (a function attribute, set once per device): make one un-captured call of the same entry
+ *     point with the same shape on that device before capturing it.
  */
 #ifndef HINM_H
 #define HINM_H
@@ -292,6 +300,14 @@ hinm_status hinm_spmm_prepared(const hinm_shape* shape, int32_t N, const void* p
                                const void* X, int64_t ldx, void* Y, int64_t ldy, uint32_t flags,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement aid: which kernel(s) hinm_spmm_prepared would launch for this shape, N, leading
+ * dimensions and flags, as text in `text` (NUL-terminated, truncated to text_bytes): one entry per
+ * launch, "name<template configuration> grid=... block=...", entries separated by "; ".  *launches
+ * (may be NULL) receives their number.  Launches nothing and touches no device; returns what
+ * hinm_spmm_prepared would return for such a call with valid pointers and a sufficient workspace. */
+hinm_status hinm_spmm_prepared_plan(const hinm_shape* shape, int32_t N, int64_t ldx, int64_t ldy,
+                                    uint32_t flags, char* text, size_t text_bytes, int32_t* launches);
+
 typedef struct {
   hinm_shape shape;
   const void* vals;       /* canonical arrays; may be NULL when `prepared` is given */
@@ -308,7 +324,9 @@ typedef struct {
 hinm_status hinm_chain_sizes(int32_t L, const hinm_layer* layers, int32_t N, size_t* scratch_bytes);
 
 /* Section 3.2 ("maintaining layer consistency"): L consecutive layers, layer
- * l+1's K equal to layer l's M and the same dtype.  Every layer writes its
+ * l+1's K equal to layer l's M and the same dtype.  Every layer's call is validated
+ * (shape, leading dimensions, pinned kernel against shape) before the first launch, so
+ * an error status means nothing was enqueued, HINM_ERR_DEVICE excepted.  Every layer writes its
  * output rows in its own pi_out order and the next layer reads them through
  * its own pi_in; no permute kernel runs in between.  Intermediates are rounded
  * to the storage type.  `scratch` is 256-byte aligned device memory. */

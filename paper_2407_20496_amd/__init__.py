@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     hinm_pack_sizes, hinm_pack, hinm_pack_static, PACK_STATIC_MAX_SCORES, hinm_pack_ordered, hinm_pack_scored, hinm_pack_vectors, hinm_unpack, hinm_spmm,
     hinm_spmm_vectors, hinm_icp_sizes, hinm_icp_search, hinm_ocp_sizes, hinm_ocp_search, hinm_ocp_cluster_sizes, hinm_ocp_cluster,
     hinm_chain_sizes, hinm_chain,
-    hinm_prepare_sizes, hinm_prepare, hinm_spmm_prepared_workspace, hinm_spmm_prepared,
+    hinm_prepare_sizes, hinm_prepare, hinm_spmm_prepared_workspace, hinm_spmm_prepared, hinm_spmm_prepared_plan,
     hinm_status_str, hinm_version,
+    calib_symbols, hinm_calib_copy, hinm_calib_fill, hinm_calib_read, hinm_calib_scatter_rows, hinm_calib_smfmac,
+    hinm_calib_empty, hinm_calib_lds_stream,
 )

@@ -39,8 +39,14 @@ def exported_symbols() -> Tuple[str, ...]:
     return ("hinm_pack_sizes", "hinm_pack", "hinm_pack_static", "hinm_pack_ordered", "hinm_pack_scored", "hinm_pack_vectors",
             "hinm_icp_sizes", "hinm_icp_search", "hinm_ocp_sizes", "hinm_ocp_search",
             "hinm_ocp_cluster_sizes", "hinm_ocp_cluster", "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_prepare_sizes", "hinm_prepare",
-            "hinm_spmm_prepared_workspace", "hinm_spmm_prepared", "hinm_chain_sizes", "hinm_chain",
-            "hinm_status_str", "hinm_version")
+            "hinm_spmm_prepared_workspace", "hinm_spmm_prepared", "hinm_spmm_prepared_plan", "hinm_chain_sizes",
+            "hinm_chain", "hinm_status_str", "hinm_version") + calib_symbols()
+
+
+def calib_symbols() -> Tuple[str, ...]:
+    """Entry points include/hinm_calib.h declares (measurement aids)."""
+    return ("hinm_calib_copy", "hinm_calib_fill", "hinm_calib_read", "hinm_calib_scatter_rows", "hinm_calib_smfmac",
+            "hinm_calib_empty", "hinm_calib_lds_stream")
 
 
 def load_library():
@@ -92,10 +98,23 @@ def load_library():
     lib.hinm_spmm_prepared_workspace.argtypes = [sp, C.c_int32, szp]
     lib.hinm_spmm_prepared.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                        C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.hinm_spmm_prepared_plan.argtypes = [sp, C.c_int32, C.c_int64, C.c_int64, C.c_uint32, C.c_char_p, C.c_size_t,
+                                            C.POINTER(C.c_int32)]
+    lib.hinm_spmm_prepared_plan.restype = C.c_int
     for name in ("hinm_pack_sizes", "hinm_pack", "hinm_pack_static", "hinm_pack_ordered", "hinm_pack_scored", "hinm_pack_vectors",
                  "hinm_icp_sizes", "hinm_icp_search", "hinm_ocp_sizes", "hinm_ocp_search",
                  "hinm_ocp_cluster_sizes", "hinm_ocp_cluster", "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_chain_sizes", "hinm_chain",
                  "hinm_prepare_sizes", "hinm_prepare", "hinm_spmm_prepared_workspace", "hinm_spmm_prepared"):
+        getattr(lib, name).restype = C.c_int
+    lib.hinm_calib_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+    lib.hinm_calib_fill.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+    lib.hinm_calib_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.hinm_calib_scatter_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_int32,
+                                            C.c_void_p]
+    lib.hinm_calib_smfmac.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+    lib.hinm_calib_empty.argtypes = [C.c_void_p]
+    lib.hinm_calib_lds_stream.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p]
+    for name in calib_symbols():
         getattr(lib, name).restype = C.c_int
     lib.hinm_status_str.argtypes = [C.c_int]
     lib.hinm_status_str.restype = C.c_char_p
@@ -306,6 +325,55 @@ def hinm_spmm_prepared(M, K, V, Kv, dtype, N, prepared, X, ldx, Y, ldy, flags=0,
     _check(lib.hinm_spmm_prepared(C.byref(_shape(M, K, V, Kv, dtype)), int(N), _ptr(prepared), _ptr(X), int(ldx),
                                   _ptr(Y), int(ldy), int(flags), _ptr(workspace), int(workspace_bytes),
                                   _stream(stream)), "hinm_spmm_prepared")
+
+
+def hinm_spmm_prepared_plan(M, K, V, Kv, dtype, N, ldx, ldy, flags=0) -> Tuple[str, int]:
+    """(description of the kernel launches hinm_spmm_prepared would make, their number)."""
+    lib = load_library()
+    buf = C.create_string_buffer(1024)
+    n = C.c_int32(0)
+    _check(lib.hinm_spmm_prepared_plan(C.byref(_shape(M, K, V, Kv, dtype)), int(N), int(ldx), int(ldy), int(flags),
+                                       buf, len(buf), C.byref(n)), "hinm_spmm_prepared_plan")
+    return buf.value.decode(), int(n.value)
+
+
+# ---- measurement aids (include/hinm_calib.h) -------------------------------------------------------
+
+def hinm_calib_copy(src, dst, nbytes, nontemporal=False, stream=None) -> None:
+    _check(load_library().hinm_calib_copy(_ptr(src), _ptr(dst), int(nbytes), int(bool(nontemporal)), _stream(stream)),
+           "hinm_calib_copy")
+
+
+def hinm_calib_fill(dst, nbytes, nontemporal=False, stream=None) -> None:
+    _check(load_library().hinm_calib_fill(_ptr(dst), int(nbytes), int(bool(nontemporal)), _stream(stream)),
+           "hinm_calib_fill")
+
+
+def hinm_calib_read(src, nbytes, sink, nontemporal=False, stream=None) -> None:
+    _check(load_library().hinm_calib_read(_ptr(src), int(nbytes), int(bool(nontemporal)), _ptr(sink), _stream(stream)),
+           "hinm_calib_read")
+
+
+def hinm_calib_scatter_rows(dst, M, N, ld, rows, piece_bytes, stream=None) -> None:
+    _check(load_library().hinm_calib_scatter_rows(_ptr(dst), int(M), int(N), int(ld), _ptr(rows), int(piece_bytes),
+                                                  _stream(stream)), "hinm_calib_scatter_rows")
+
+
+def hinm_calib_smfmac(dtype, iterations, sink, stream=None) -> float:
+    """Enqueues the loop; returns the launch's flops counted on stored values."""
+    flops = C.c_double(0.0)
+    _check(load_library().hinm_calib_smfmac(_dtype_code(dtype), int(iterations), _ptr(sink), C.byref(flops),
+                                            _stream(stream)), "hinm_calib_smfmac")
+    return float(flops.value)
+
+
+def hinm_calib_empty(stream=None) -> None:
+    _check(load_library().hinm_calib_empty(_stream(stream)), "hinm_calib_empty")
+
+
+def hinm_calib_lds_stream(region, region_bytes, passes, workgroups, stream=None) -> None:
+    _check(load_library().hinm_calib_lds_stream(_ptr(region), int(region_bytes), int(passes), int(workgroups),
+                                                _stream(stream)), "hinm_calib_lds_stream")
 
 
 @dataclass

@@ -308,10 +308,11 @@ hinm_status hinm_spmm_vectors(const hinm_shape* shape, int32_t N, const void* va
 }
 
 static hinm_status check_prepared_call(const hinm_shape* shape, int32_t N, const void* prepared, const void* X,
-                                       int64_t ldx, const void* Y, int64_t ldy, uint32_t flags);
+                                       int64_t ldx, const void* Y, int64_t ldy, uint32_t flags, void* workspace,
+                                       size_t workspace_bytes);
 static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
                                 void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes,
-                                hipStream_t stream);
+                                hipStream_t stream, LaunchPlan* plan);
 
 static hinm_status check_chain(int32_t L, const hinm_layer* layers, int32_t N, size_t* bytes_per_buffer) {
   if (!layers) return HINM_ERR_NULL;
@@ -357,7 +358,7 @@ hinm_status hinm_chain(int32_t L, const hinm_layer* layers, int32_t N, const voi
     void* out = (l == L - 1) ? Y : scratch;
     if (layers[l].prepared)
       st = check_prepared_call(&layers[l].shape, N, layers[l].prepared, in, l == 0 ? ldx : ldh, out,
-                               l == L - 1 ? ldy : ldh, layers[l].flags);
+                               l == L - 1 ? ldy : ldh, layers[l].flags, nullptr, 0);
     else
       st = check_spmm(&layers[l].shape, N, layers[l].vals, layers[l].nm_idx, layers[l].vec_idx, in,
                       l == 0 ? ldx : ldh, out, l == L - 1 ? ldy : ldh, layers[l].flags);
@@ -373,7 +374,7 @@ hinm_status hinm_chain(int32_t L, const hinm_layer* layers, int32_t N, const voi
     const hinm_layer& ly = layers[l];
     if (ly.prepared) {
       st = run_prepared(&ly.shape, N, ly.prepared, in, ld_in, out, ld_out, ly.flags, nullptr, 0,
-                        static_cast<hipStream_t>(stream));
+                        static_cast<hipStream_t>(stream), nullptr);
     } else {
       SpmmArgs a{ly.shape, N, ly.vals, ly.nm_idx, ly.vec_idx, ly.pi_in, ly.pi_out, in, ld_in, out, ld_out,
                  (ly.flags & HINM_EPI_RELU) != 0, (ly.flags & HINM_OUT_F32) != 0};
@@ -419,25 +420,19 @@ hinm_status hinm_spmm_prepared_workspace(const hinm_shape* shape, int32_t N, siz
   return HINM_OK;
 }
 
-static hinm_status check_prepared_call(const hinm_shape* shape, int32_t N, const void* prepared, const void* X,
-                                       int64_t ldx, const void* Y, int64_t ldy, uint32_t flags) {
-  size_t need = 0;
-  hinm_status st = hinm_prepare_sizes(shape, &need);
-  if (st != HINM_OK) return st;
-  if (!prepared || !X || !Y) return HINM_ERR_NULL;
-  if (N <= 0 || ldx < N || ldy < N) return HINM_ERR_SHAPE;
-  if (N > 1 && (ldx % 8 != 0 || ldy % 8 != 0)) return HINM_ERR_SHAPE;
-  if (!aligned(prepared, 256) || !aligned(X, 16) || !aligned(Y, 16)) return HINM_ERR_SHAPE;
-  if (flags & ~(uint32_t)(HINM_EPI_RELU | HINM_OUT_F32 | HINM_VARIANT_MASK)) return HINM_ERR_UNSUPPORTED;
-  return HINM_OK;
+// Which kernel family a prepared call runs on; everything that can make the call fail is decided here, on the
+// host, before anything is launched (hinm_chain validates every layer with it before its first launch).
+enum class PreparedRoute { Rows16, Skinny, Panel, Tile };
+
+static PreparedArgs prepared_args(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
+                                  void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes) {
+  return PreparedArgs{*shape, N, prepared, X, ldx, Y, ldy, (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0,
+                      (int)((flags & HINM_VARIANT_MASK) >> HINM_VARIANT_SHIFT), workspace, workspace_bytes};
 }
 
-static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
-                                void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes,
-                                hipStream_t stream) {
-  PreparedArgs a{*shape, N, prepared, X, ldx, Y, ldy, (flags & HINM_EPI_RELU) != 0, (flags & HINM_OUT_F32) != 0,
-                 (int)((flags & HINM_VARIANT_MASK) >> HINM_VARIANT_SHIFT), workspace, workspace_bytes};
-  hipError_t e;
+static hinm_status route_prepared(const PreparedArgs& a, PreparedRoute* route) {
+  const hinm_shape* shape = &a.s;
+  const int32_t N = a.N;
   // up to 16 columns: 16-row workgroups on the 16x16x64 form (measured faster than the 32-row kernel on every
   // decode shape tried, by 8-10 % with 344 row blocks of 32 and by 15-37 % with 128); variant 11 pins it for any N, 19 its form with
   // the input rows resident in LDS (16 columns only)
@@ -468,16 +463,52 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
   }
   if (a.tile_variant == 11 || a.tile_variant == 19 || (a.tile_variant == 0 && few_columns)) {
     if ((N + 15) / 16 > 65535) return HINM_ERR_UNSUPPORTED;
-    e = launch_spmm_rows16_prepared(a, stream);
+    *route = PreparedRoute::Rows16;
   } else if (N <= 32 && (a.tile_variant == 0 || a.tile_variant == 12)) {  // variant 12 pins the 32-row skinny kernel
     const size_t need = skinny_prepared_workspace_bytes(*shape, N);
-    if (need > 0 && (!workspace || workspace_bytes < need || !aligned(workspace, 256))) return HINM_ERR_WORKSPACE;
-    e = launch_spmm_skinny_prepared(a, stream);
+    if (need > 0 && (!a.workspace || a.workspace_bytes < need || !aligned(a.workspace, 256)))
+      return HINM_ERR_WORKSPACE;
+    *route = PreparedRoute::Skinny;
   } else {
-    if (N == 1 || ldx % 8 != 0 || ldy % 8 != 0 || a.tile_variant == 12) return HINM_ERR_UNSUPPORTED;
+    if (N == 1 || a.ldx % 8 != 0 || a.ldy % 8 != 0 || a.tile_variant == 12) return HINM_ERR_UNSUPPORTED;
     const bool panel = (a.tile_variant == 15) || (a.tile_variant == 0 && spmm_panel_prepared_preferred(a));
     if (panel && !spmm_panel_prepared_supported(a)) return HINM_ERR_UNSUPPORTED;
-    e = panel ? launch_spmm_panel_prepared(a, stream) : launch_spmm_tile_prepared(a, stream);
+    *route = panel ? PreparedRoute::Panel : PreparedRoute::Tile;
+  }
+  return HINM_OK;
+}
+
+static hinm_status check_prepared_call(const hinm_shape* shape, int32_t N, const void* prepared, const void* X,
+                                       int64_t ldx, const void* Y, int64_t ldy, uint32_t flags, void* workspace,
+                                       size_t workspace_bytes) {
+  size_t need = 0;
+  hinm_status st = hinm_prepare_sizes(shape, &need);
+  if (st != HINM_OK) return st;
+  if (!prepared || !X || !Y) return HINM_ERR_NULL;
+  if (N <= 0 || ldx < N || ldy < N) return HINM_ERR_SHAPE;
+  if (N > 1 && (ldx % 8 != 0 || ldy % 8 != 0)) return HINM_ERR_SHAPE;
+  if (!aligned(prepared, 256) || !aligned(X, 16) || !aligned(Y, 16)) return HINM_ERR_SHAPE;
+  if (flags & ~(uint32_t)(HINM_EPI_RELU | HINM_OUT_F32 | HINM_VARIANT_MASK)) return HINM_ERR_UNSUPPORTED;
+  PreparedRoute route;
+  return route_prepared(prepared_args(shape, N, prepared, X, ldx, const_cast<void*>(Y), ldy, flags, workspace,
+                                      workspace_bytes), &route);
+}
+
+// The call has passed check_prepared_call.
+static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
+                                void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes,
+                                hipStream_t stream, LaunchPlan* plan) {
+  PreparedArgs a = prepared_args(shape, N, prepared, X, ldx, Y, ldy, flags, workspace, workspace_bytes);
+  a.plan = plan;
+  PreparedRoute route;
+  hinm_status st = route_prepared(a, &route);
+  if (st != HINM_OK) return st;
+  hipError_t e = hipSuccess;
+  switch (route) {
+    case PreparedRoute::Rows16: e = launch_spmm_rows16_prepared(a, stream); break;
+    case PreparedRoute::Skinny: e = launch_spmm_skinny_prepared(a, stream); break;
+    case PreparedRoute::Panel: e = launch_spmm_panel_prepared(a, stream); break;
+    case PreparedRoute::Tile: e = launch_spmm_tile_prepared(a, stream); break;
   }
   return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
@@ -485,10 +516,24 @@ static hinm_status run_prepared(const hinm_shape* shape, int32_t N, const void* 
 hinm_status hinm_spmm_prepared(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
                                void* Y, int64_t ldy, uint32_t flags, void* workspace, size_t workspace_bytes,
                                void* stream) {
-  hinm_status st = check_prepared_call(shape, N, prepared, X, ldx, Y, ldy, flags);
+  hinm_status st = check_prepared_call(shape, N, prepared, X, ldx, Y, ldy, flags, workspace, workspace_bytes);
   if (st != HINM_OK) return st;
   return run_prepared(shape, N, prepared, X, ldx, Y, ldy, flags, workspace, workspace_bytes,
-                      static_cast<hipStream_t>(stream));
+                      static_cast<hipStream_t>(stream), nullptr);
+}
+
+hinm_status hinm_spmm_prepared_plan(const hinm_shape* shape, int32_t N, int64_t ldx, int64_t ldy, uint32_t flags,
+                                    char* text, size_t text_bytes, int32_t* launches) {
+  if (!text || text_bytes == 0) return HINM_ERR_NULL;
+  text[0] = 0;
+  // stand-ins with the alignment of real buffers: a dry run dereferences nothing
+  void* const fake = reinterpret_cast<void*>(uintptr_t{1} << 20);
+  hinm_status st = check_prepared_call(shape, N, fake, fake, ldx, fake, ldy, flags, fake, ~size_t{0});
+  if (st != HINM_OK) return st;
+  LaunchPlan plan{text, text_bytes};
+  st = run_prepared(shape, N, fake, fake, ldx, fake, ldy, flags, fake, ~size_t{0}, nullptr, &plan);
+  if (launches) *launches = plan.launches;
+  return st;
 }
 
 const char* hinm_status_str(hinm_status s) {

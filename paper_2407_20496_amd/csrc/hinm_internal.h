@@ -5,6 +5,8 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <cstdarg>
+#include <cstdio>
 
 #include "hinm.h"
 
@@ -26,6 +28,30 @@ inline hipError_t raise_lds_limit(int bytes) {
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e == hipSuccess && dev < 64) done.fetch_or(uint64_t{1} << dev, std::memory_order_relaxed);
   return e;
+}
+
+// ---- host: dry run of a launcher ------------------------------------------------------------------
+// With a plan attached to its arguments a launcher records which kernel it would launch, with which
+// template configuration and launch shape, and launches nothing (hinm_spmm_prepared_plan).
+struct LaunchPlan {
+  char* text;       // caller's buffer, always NUL-terminated
+  size_t capacity;
+  size_t length = 0;
+  int launches = 0;
+};
+inline void plan_record(LaunchPlan* p, const char* fmt, ...) {
+  if (p->launches > 0 && p->length + 2 < p->capacity) {
+    p->text[p->length++] = ';';
+    p->text[p->length++] = ' ';
+    p->text[p->length] = 0;
+  }
+  ++p->launches;
+  if (p->length + 1 >= p->capacity) return;
+  va_list ap;
+  va_start(ap, fmt);
+  const int n = vsnprintf(p->text + p->length, p->capacity - p->length, fmt, ap);
+  va_end(ap);
+  if (n > 0) p->length = (p->length + (size_t)n < p->capacity) ? p->length + (size_t)n : p->capacity - 1;
 }
 
 // ---- 16-bit storage helpers (device) ---------------------------------------------------------
@@ -196,6 +222,7 @@ struct PreparedArgs {
   int tile_variant;  // 0 = choose by shape; 1.. = a fixed (column block, stage size, depth) choice
   void* workspace;
   size_t workspace_bytes;
+  LaunchPlan* plan = nullptr;  // non-NULL: record the launches instead of making them
 };
 
 hipError_t launch_spmm_tile_prepared(const PreparedArgs& a, hipStream_t stream);

@@ -248,9 +248,14 @@ template <int DT, int RB, int WAVES>
 hipError_t launch_waves(const PreparedArgs& a, int n_blocks, int tile_groups, hipStream_t stream) {
   const PreparedLayout L = prepared_layout(a.s);
   constexpr auto kernel = spmm_panel_prepared_kernel<DT, RB, WAVES>;
+  const int nb8 = (n_blocks + 7) / 8 * 8;  // ids are laid out in groups of 8 column blocks
+  if (a.plan) {
+    plan_record(a.plan, "spmm_panel_prepared_kernel<DT=%d,RB=%d,WAVES=%d> grid=%d block=%d lds=%d", DT, RB, WAVES,
+                nb8 * tile_groups, WAVES * 64, (int)panel_lds_bytes(a.s.K, WAVES));
+    return hipSuccess;
+  }
   if (hipError_t e = raise_lds_limit<kernel>(160 * 1024); e != hipSuccess) return e;
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
-  const int nb8 = (n_blocks + 7) / 8 * 8;  // ids are laid out in groups of 8 column blocks
   kernel<<<dim3((unsigned)(nb8 * tile_groups)), WAVES * 64, panel_lds_bytes(a.s.K, WAVES), stream>>>(
       base + L.a_offset, reinterpret_cast<const uint32_t*>(base + L.panel_offset),
       reinterpret_cast<const int32_t*>(base + L.pi_out_offset), static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy,

@@ -292,7 +292,11 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, int blocks_per
   const int col_blocks = (a.N + kCols - 1) / kCols;
 #define HINM_ROWS16(MODE, GRID_Y, X_PTR, Y_OFF, LDS) HINM_ROWS16_CB(MODE, 1, KB, GRID_Y, X_PTR, Y_OFF, LDS)
 #define HINM_ROWS16_CB(MODE, CBV, KBV, GRID_Y, X_PTR, Y_OFF, LDS)                                                \
-  spmm_rows16_prepared_kernel<DT, NW, MODE, KBV, RBW, CBV>                                                       \
+  if (a.plan)                                                                                                    \
+    plan_record(a.plan, "spmm_rows16_prepared_kernel<DT=%d,NW=%d,XMODE=%d,KB=%d,RBW=%d,CB=%d> grid=%dx%d block=%d", \
+                DT, NW, MODE, KBV, RBW, CBV, a.s.M / (kRows * RBW), (int)(GRID_Y), NW * 64);                     \
+  else                                                                                                           \
+    spmm_rows16_prepared_kernel<DT, NW, MODE, KBV, RBW, CBV>                                                     \
       <<<dim3(a.s.M / (kRows * RBW), GRID_Y), NW * 64, LDS, stream>>>(                                           \
           base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),                           \
           reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset, X_PTR, a.ldx,          \
@@ -307,7 +311,7 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, int blocks_per
                        a.s.K <= 8 * kXPieces * NW * 64 && x_bytes <= (size_t)kXLdsMaxBytes && L.S > 4 * NW;
     if (stage) {
       // slabs (static) plus the vector (dynamic) can exceed the default 64 KB of a workgroup
-      if (raise_lds_limit<spmm_rows16_prepared_kernel<DT, NW, 3, KB, RBW>>(kXLdsMaxBytes) != hipSuccess)
+      if (!a.plan && raise_lds_limit<spmm_rows16_prepared_kernel<DT, NW, 3, KB, RBW>>(kXLdsMaxBytes) != hipSuccess)
         return;  // the error stays pending and is reported by the caller's hipGetLastError
       HINM_ROWS16(3, 1, x, 0, x_bytes);
     } else {
@@ -326,22 +330,36 @@ void launch_modes(const PreparedArgs& a, const PreparedLayout& L, int blocks_per
       return;
     }
   }
-  if (a.ldx % 8 == 0) HINM_ROWS16(1, col_blocks, x, 0, 0);
-  else HINM_ROWS16(0, col_blocks, x, 0, 0);
+  if (a.ldx % 8 == 0) {
+    HINM_ROWS16(1, col_blocks, x, 0, 0);
+  } else {
+    HINM_ROWS16(0, col_blocks, x, 0, 0);
+  }
 #undef HINM_ROWS16
 #undef HINM_ROWS16_CB
 }
 
 // The layer's input rows resident in LDS (XMODE 4): 16 columns, 64 rows per workgroup.
 inline size_t resident_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 1024 + 32; }
+// The same region later takes the waves' partial tiles (four 16 x 16 fp32 tiles = 4096 bytes per wave), which
+// for short input vectors is the larger of the two.
+inline size_t resident_dynamic_lds_bytes(int K, int NW) {
+  const size_t partials = (size_t)NW * 4 * kRows * kCols * 4;
+  return resident_lds_bytes(K) > partials ? resident_lds_bytes(K) : partials;
+}
 
 template <int DT, int NW>
 void launch_resident(const PreparedArgs& a, const PreparedLayout& L, hipStream_t stream) {
   constexpr auto kernel = spmm_rows16_prepared_kernel<DT, NW, 4, 4, 4>;
+  if (a.plan) {
+    plan_record(a.plan, "spmm_rows16_prepared_kernel<DT=%d,NW=%d,XMODE=4,KB=4,RBW=4,CB=1> grid=%dx1 block=%d lds=%d", DT,
+                NW, a.s.M / 64, NW * 64, (int)resident_dynamic_lds_bytes(a.s.K, NW));
+    return;
+  }
   if (raise_lds_limit<kernel>(160 * 1024 - NW * kSlabBytes) != hipSuccess)
     return;  // the error stays pending and is reported by the caller's hipGetLastError
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
-  kernel<<<dim3(a.s.M / 64, 1), NW * 64, resident_lds_bytes(a.s.K), stream>>>(
+  kernel<<<dim3(a.s.M / 64, 1), NW * 64, resident_dynamic_lds_bytes(a.s.K, NW), stream>>>(
       base + L.a_offset, reinterpret_cast<const int32_t*>(base + L.gather_offset),
       reinterpret_cast<const int32_t*>(base + L.pi_out_offset), base + L.zero_offset,
       static_cast<const uint16_t*>(a.X), a.ldx, a.Y, a.ldy, a.s.V, L.RB, L.S, a.N, a.s.K, a.relu, a.out_f32);
@@ -440,12 +458,13 @@ bool spmm_rows16_resident_supported(const PreparedArgs& a) {
   if (a.N != 16 || a.ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(a.X) & 15u) != 0) return false;
   if (a.s.V % 64 != 0 || L.S > 32 || a.tile_variant == 11) return false;
   const int NW = L.S <= 16 ? 4 : 8;
-  return resident_lds_bytes(a.s.K) + (size_t)NW * kSlabBytes <= 160 * 1024;
+  return resident_dynamic_lds_bytes(a.s.K, NW) + (size_t)NW * kSlabBytes <= 160 * 1024;
 }
 
 hipError_t launch_spmm_rows16_prepared(const PreparedArgs& a, hipStream_t stream) {
   if (a.s.dtype == HINM_F16) launch_dt<HINM_F16>(a, stream);
   else launch_dt<HINM_BF16>(a, stream);
+  if (a.plan) return hipSuccess;  // a dry run launched nothing
   return hipGetLastError();
 }
 

@@ -225,6 +225,11 @@ template <int DT, int NWV, int KB, int NG, int RBW, bool XS>
 void launch_kernel(const PreparedArgs& a, const PreparedLayout& L, size_t lds_bytes, hipStream_t stream) {
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   constexpr auto kernel = spmm_skinny_prepared_kernel<DT, NWV, KB, NG, RBW, XS>;
+  if (a.plan) {
+    plan_record(a.plan, "spmm_skinny_prepared_kernel<DT=%d,NWV=%d,KB=%d,NG=%d,RBW=%d,XS=%d> grid=%dx%d block=%d lds=%d", DT,
+                NWV, KB, NG, RBW, (int)XS, L.RB / RBW, L.T, NWV * 64, (int)lds_bytes);
+    return;
+  }
   if (raise_lds_limit<kernel>((int)(NWV * kSlabBytes + kXLdsMaxBytes)) != hipSuccess)
     return;  // the error stays pending and is reported by the caller's hipGetLastError
   kernel<<<dim3(L.RB / RBW, L.T), NWV * 64, lds_bytes, stream>>>(
@@ -290,6 +295,7 @@ size_t skinny_prepared_workspace_bytes(const hinm_shape&, int) { return 0; }
 hipError_t launch_spmm_skinny_prepared(const PreparedArgs& a, hipStream_t stream) {
   if (a.s.dtype == HINM_F16) launch_dt<HINM_F16>(a, stream);
   else launch_dt<HINM_BF16>(a, stream);
+  if (a.plan) return hipSuccess;  // a dry run launched nothing
   return hipGetLastError();
 }
 

@@ -329,6 +329,11 @@ hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream, int tile_base =
   const int64_t work = (int64_t)n_blocks * T;
   const int work_per_xcd = (int)((work + 7) / 8);
   constexpr auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST, WC>;
+  if (a.plan) {
+    plan_record(a.plan, "spmm_tile_prepared_kernel<DT=%d,RB=%d,NB=%d,KSUB=%d,ST=%d,WC=%d> tiles=%d..%d grid=%d block=%d lds=%d",
+                DT, RB, NB, KSUB, ST, WC, tile_base, tile_base + T - 1, work_per_xcd * 8, C::THREADS, C::LDS_BYTES);
+    return hipSuccess;
+  }
   if (hipError_t e = raise_lds_limit<kernel>(C::LDS_BYTES); e != hipSuccess) return e;
   const uint8_t* base = static_cast<const uint8_t*>(a.prepared);
   const size_t tb = (size_t)tile_base;

@@ -14,9 +14,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "hinm.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hinm_[a-z_]+)\s*\(", text)))
+    """Every function declared by a header under include/."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if header.endswith(".h"):
+            text = open(os.path.join(inc, header)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names.update(re.findall(r"\b(hinm_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -141,6 +147,53 @@ def test_pack_static_rejects_layers_beyond_its_array_before_touching_the_device(
     assert lib.hinm_pack_static(C.byref(ok_shape), fake, fake + 2, fake, fake, None) == 2
     text = open(os.path.join(ROOT, "include", "hinm.h")).read()
     assert f"#define HINM_PACK_STATIC_MAX_SCORES {hinm.PACK_STATIC_MAX_SCORES}" in text
+
+
+def test_plan_query_names_the_kernels_without_a_device():
+    text, n = hinm.hinm_spmm_prepared_plan(16384, 16384, 128, 8192, "bf16", 8192, 8192, 8192)
+    assert n == 1 and text.startswith("spmm_tile_prepared_kernel<") and "NB=512" in text
+    text, n = hinm.hinm_spmm_prepared_plan(11008, 4096, 128, 2048, "bf16", 2048, 2048, 2048)
+    assert n == 2 and text.count("spmm_tile_prepared_kernel") == 2 and "; " in text   # whole rounds + remainder
+    text, n = hinm.hinm_spmm_prepared_plan(3072, 768, 64, 384, "f16", 4096, 4096, 4096)
+    assert n == 1 and text.startswith("spmm_panel_prepared_kernel<")
+    text, n = hinm.hinm_spmm_prepared_plan(4096, 11008, 128, 5504, "bf16", 1, 1, 1)
+    assert n == 1 and text.startswith("spmm_rows16_prepared_kernel<")
+    # a pinned kernel that does not fit the shape is refused here exactly as by the product call
+    with pytest.raises(hinm.HinmError) as err:
+        hinm.hinm_spmm_prepared_plan(128, 8192, 128, 4096, "f16", 16, 16, 16, flags=19 << 16)
+    assert err.value.status == 5
+    with pytest.raises(hinm.HinmError) as err:
+        hinm.hinm_spmm_prepared_plan(256, 256, 16, 128, "f16", 64, 64, 64)       # V = 16: no prepared form
+    assert err.value.status == 5
+
+
+def test_chain_rejects_a_pinned_kernel_that_does_not_fit_before_launching_anything():
+    lib = hinm.load_library()
+    fake = 0x100000
+    ok = binding._Layer(binding._Shape(256, 256, 64, 128, 0), None, None, None, None, None, 0, fake)
+    # second layer pins the LDS-resident 16-column kernel (variant 19) at N = 8: unsupported
+    bad = binding._Layer(binding._Shape(256, 256, 64, 128, 0), None, None, None, None, None, 19 << 16, fake)
+    two = (binding._Layer * 2)(ok, bad)
+    assert lib.hinm_chain(2, two, 8, fake, 8, fake, 8, fake, 1 << 20, None) == 5
+    # ... and the tile branch at one column
+    bad1 = binding._Layer(binding._Shape(256, 256, 64, 128, 0), None, None, None, None, None, 3 << 16, fake)
+    two = (binding._Layer * 2)(ok, bad1)
+    assert lib.hinm_chain(2, two, 1, fake, 1, fake, 1, fake, 1 << 20, None) == 5
+
+
+def test_calibration_entry_points_validate_before_launching():
+    lib = hinm.load_library()
+    fake = 0x100000
+    assert lib.hinm_calib_copy(None, fake, 1024, 0, None) == 1
+    assert lib.hinm_calib_copy(fake, fake + 4096, 1000, 0, None) == 2          # not a multiple of 16
+    assert lib.hinm_calib_copy(fake + 8, fake + 4096, 1024, 0, None) == 2       # misaligned
+    assert lib.hinm_calib_fill(None, 1024, 0, None) == 1
+    assert lib.hinm_calib_read(fake, 1024, 0, None, None) == 1
+    assert lib.hinm_calib_scatter_rows(fake, 64, 256, 256, None, 96, None) == 2   # piece size
+    assert lib.hinm_calib_scatter_rows(fake, 64, 96, 96, None, 128, None) == 2    # row bytes not a multiple of the piece
+    assert lib.hinm_calib_smfmac(5, 10, fake, None, None) == 3
+    assert lib.hinm_calib_smfmac(0, 0, fake, None, None) == 2
+    assert lib.hinm_calib_lds_stream(fake, 1000, 1, 1, None) == 2
 
 
 def test_chain_validation():

@@ -219,6 +219,8 @@ def _padding_may_hold_anything(case, N, ld, variants):
     (384, 1000, 128, 504, "bf16"),    # K % 32 != 0, Kv % 64 != 0: clamped copies, padded kept columns
     (128, 4096, 128, 2048, "f16"),    # 32 steps: the largest input that fits beside eight slabs
     (192, 2048, 64, 1024, "bf16"),
+    (128, 256, 64, 128, "f16"),       # two steps, 8 KB of input rows: the waves' partial tiles (16 KB) need more LDS
+    (128, 640, 128, 576, "bf16"),     # nine steps over four waves, 20 KB of input rows
 ])
 def test_prepared_sixteen_columns_input_resident_in_lds(M, K, V, Kv, dtype):
     case = synth.small_case(M, K, V, Kv, 16, dtype, 86)

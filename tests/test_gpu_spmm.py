@@ -151,38 +151,37 @@ def test_c2_full():
     _check_full(c, c.N, [0])
 
 
-def _check_sampled(case, N, n_rows=24, n_cols=64, X_dev=None):
-    """Full-size layers: sampled outputs computed one by one by the oracle, plus
-    the whole-matrix agreement of the fast kernel with the plain GPU kernel on a
-    column slice is covered by the small cases; here rows are drawn from the first,
-    a middle and the last tile and columns from every column block."""
+def _check_sampled(case, N, rows_per_tile=2, whole_tiles=(0,), X_dev=None):
+    """Full-size layers through hinm_spmm on the canonical arrays: the pack is compared with the oracle on
+    every tile, and the product on `rows_per_tile` rows of every tile plus all rows of `whole_tiles`, all N
+    columns of each (so every tile and every column block of the launch is covered), computed by the oracle's
+    row form."""
     from tests import gpu_util as gu
     Wb = case.weights()
     p = gu.gpu_pack(Wb, case.dtype, case.V, case.Kv)
     vals, nm, vec = p.host()
     rng = np.random.default_rng(case.M + N)
-    tiles = [0, case.T // 2, case.T - 1]
-    rows = np.concatenate([t * case.V + rng.choice(case.V, n_rows // 3, replace=False) for t in tiles])
-    o_vals, o_nm, o_vec = [], [], []
+    rows = []
+    for t in range(case.T):
+        pick = np.arange(case.V) if t in whole_tiles else np.sort(rng.choice(case.V, rows_per_tile, replace=False))
+        rows.extend(t * case.V + pick)
+    rows = np.array(rows)
     Wh_rows = np.zeros((len(rows), case.K), dtype=np.uint16)
-    for t in tiles:
+    for t in range(case.T):
         sl = slice(t * case.V, (t + 1) * case.V)
         ov, on, oc = orc.pack(Wb[sl], case.dtype, case.V, case.Kv)
-        assert np.array_equal(vec[t], oc[0]) and np.array_equal(vals[sl], ov) and np.array_equal(nm[sl], on)
+        assert np.array_equal(vec[t], oc[0]) and np.array_equal(vals[sl], ov) and np.array_equal(nm[sl], on), f"tile {t}"
         Wh_t = orc.unpack_fast(ov, on, oc, case.V, case.K, case.V)
-        for a, r in enumerate(rows):
-            if r // case.V == t:
-                Wh_rows[a] = Wh_t[r - t * case.V]
+        sel = (rows // case.V) == t
+        Wh_rows[sel] = Wh_t[rows[sel] - t * case.V]
     Xb = case.activations(N)
-    cols = np.unique(np.concatenate([[0, N - 1], rng.choice(N, min(N, n_cols), replace=False)]))
     pi_in, pi_out = case.pi_in(), case.pi_out()
-    want = orc.product_entries(Wh_rows, Xb, case.dtype, pi_in, None, np.arange(len(rows)), cols)
+    want = orc.product_rows(Wh_rows, Xb, case.dtype, pi_in)
     got32 = gu.gpu_spmm(p, Xb, pi_in, pi_out, OUT_F32, X_dev=X_dev)
-    sub = got32[pi_out[rows]][:, cols].astype(np.float64)
-    gu.check_close(sub, want, what=f"{case.name} sampled fp32 accumulators")
+    gu.check_close(got32[pi_out[rows]].astype(np.float64), want, what=f"{case.name} sampled fp32 accumulators")
     got = gu.gpu_spmm(p, Xb, pi_in, pi_out, 0, X_dev=X_dev)
     assert np.array_equal(got, orc.round_to_storage(got32, case.dtype)), "output is not the rounded accumulator"
-    # property that holds at any size: every output row was written exactly once (poison gone, no NaN)
+    # property that holds at any size: every output row was written (the poison is NaN)
     assert np.isfinite(got32).all()
     return got32
 
@@ -234,4 +233,4 @@ def test_c4_chain_full():
 
 def test_c5_sampled():
     c = synth.c5()
-    _check_sampled(c, c.N, n_rows=12, n_cols=48)
+    _check_sampled(c, c.N, rows_per_tile=2, whole_tiles=(64,))
