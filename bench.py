@@ -134,13 +134,17 @@ def calibrate(torch, hinm, dev, dtype, quick=True):
     _, ev_ms = graph_replay_ms(torch, lambda i: hinm.hinm_calib_empty(), nodes)
     out["graph_node_floor_us"] = round(ev_ms * 1e3 / nodes, 3)
     if not quick:
-        # a compute unit drawing L2-resident data into LDS (2 MB region shared by all workgroups)
-        region = 2 << 20
-        passes = 64
-        ms = timed(lambda: hinm.hinm_calib_lds_stream(a, region, passes, 256), reps)
-        out["l2_to_lds_gbps_256_workgroups"] = round(256 * passes * region / ms / 1e6, 1)
-        ms = timed(lambda: hinm.hinm_calib_lds_stream(a, region, passes, 512), reps)
-        out["l2_to_lds_gbps_512_workgroups"] = round(512 * passes * region / ms / 1e6, 1)
+        # compute units drawing data into LDS: a 2 MB region every workgroup walks (stays in L2), and a 1 GiB region
+        # split into disjoint parts (every line comes from HBM); all 256 units at once, and 32 workgroups only
+        # (HBM far from saturated: what one unit's memory pipeline sustains at the miss latency)
+        region, chunks = 2 << 20, 16384
+        for wgs in (32, 256, 512):
+            ms = timed(lambda: hinm.hinm_calib_lds_stream(a, region, 8192, chunks, wgs), reps)
+            out[f"l2_to_lds_gbps_{wgs}_workgroups"] = round(wgs * chunks * 8192 / ms / 1e6, 1)
+        for wgs in (8, 32, 256):
+            per = (nbytes // wgs) // 8192
+            ms = timed(lambda: hinm.hinm_calib_lds_stream(a, nbytes, per * 8192, per, wgs), 3)
+            out[f"hbm_to_lds_gbps_{wgs}_workgroups"] = round(wgs * per * 8192 / ms / 1e6, 1)
         # store-only passes shaped like the C2 output (3072 x 4096 fp16): natural and permuted rows, three piece sizes
         M, N = 3072, 4096
         Ys = [torch.empty((M, N), dtype=torch.int16, device=dev) for _ in range(24)]    # 600 MB rotated

@@ -51,12 +51,15 @@ hinm_status hinm_calib_smfmac(int32_t dtype, int32_t iterations, float* sink, do
 /* One workgroup of one wave that does nothing: the cost of a launch (or of a graph node). */
 hinm_status hinm_calib_empty(void* stream);
 
-/* Every compute unit draws cache-resident data into LDS: `workgroups` workgroups of 512 lanes; each
- * copies the same region (region_bytes, a multiple of 8192, 16-byte aligned, at most 64 KiB staged at
- * a time) `passes` times with direct-to-LDS loads of 16 bytes per lane, workgroup w starting at
- * offset (w * 8192) % region_bytes.  Total bytes drawn = workgroups * passes * region_bytes. */
-hinm_status hinm_calib_lds_stream(const void* region, size_t region_bytes, int32_t passes, int32_t workgroups,
-                                  void* stream);
+/* Compute units draw data into LDS with direct-to-LDS loads of 16 bytes per lane: `workgroups` workgroups
+ * of 512 lanes; workgroup w copies chunks_per_workgroup consecutive 8 KiB chunks of the region (region_bytes,
+ * a multiple of 8192, 16-byte aligned), starting at byte (w * start_stride_bytes) % region_bytes (a
+ * multiple of 8192) and wrapping at the region's end, with eight copies per wave in flight (64 KiB per
+ * workgroup).  A small region with a small stride stays cache-resident (every workgroup walks the same
+ * bytes); a large region with start_stride_bytes = region_bytes / workgroups gives every workgroup bytes
+ * that nobody else reads.  Total bytes drawn = workgroups * chunks_per_workgroup * 8192. */
+hinm_status hinm_calib_lds_stream(const void* region, size_t region_bytes, size_t start_stride_bytes,
+                                  int64_t chunks_per_workgroup, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

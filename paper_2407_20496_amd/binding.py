@@ -113,7 +113,7 @@ def load_library():
                                             C.c_void_p]
     lib.hinm_calib_smfmac.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
     lib.hinm_calib_empty.argtypes = [C.c_void_p]
-    lib.hinm_calib_lds_stream.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p]
+    lib.hinm_calib_lds_stream.argtypes = [C.c_void_p, C.c_size_t, C.c_size_t, C.c_int64, C.c_int32, C.c_void_p]
     for name in calib_symbols():
         getattr(lib, name).restype = C.c_int
     lib.hinm_status_str.argtypes = [C.c_int]
@@ -371,9 +371,11 @@ def hinm_calib_empty(stream=None) -> None:
     _check(load_library().hinm_calib_empty(_stream(stream)), "hinm_calib_empty")
 
 
-def hinm_calib_lds_stream(region, region_bytes, passes, workgroups, stream=None) -> None:
-    _check(load_library().hinm_calib_lds_stream(_ptr(region), int(region_bytes), int(passes), int(workgroups),
-                                                _stream(stream)), "hinm_calib_lds_stream")
+def hinm_calib_lds_stream(region, region_bytes, start_stride_bytes, chunks_per_workgroup, workgroups,
+                          stream=None) -> None:
+    _check(load_library().hinm_calib_lds_stream(_ptr(region), int(region_bytes), int(start_stride_bytes),
+                                                int(chunks_per_workgroup), int(workgroups), _stream(stream)),
+           "hinm_calib_lds_stream")
 
 
 @dataclass

@@ -16,7 +16,7 @@ LIB = os.path.join(HERE, "libhinm.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["hinm_api.hip", "pack_kernels.hip", "icp_search.hip", "ocp_search.hip", "prepare.hip", "spmm_reference.hip", "spmm_skinny.hip", "spmm_tile.hip", "spmm_vectors.hip",
-           "spmm_tile_prepared.hip", "spmm_skinny_prepared.hip", "spmm_rows16_prepared.hip", "spmm_panel_prepared.hip",
+           "spmm_tile_prepared.hip",  "spmm_skinny_prepared.hip", "spmm_rows16_prepared.hip", "spmm_panel_prepared.hip",
            "calib_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -116,12 +116,12 @@ constexpr int kStreamThreads = 512;
 constexpr int kStreamChunk = 8192;       // bytes one wave-round of the workgroup copies (512 lanes x 16 bytes)
 constexpr int kStreamLdsBytes = 65536;   // LDS ring the copies land in
 __global__ __launch_bounds__(kStreamThreads) void calib_lds_stream_kernel(const uint8_t* __restrict__ region,
-                                                                          uint32_t chunks, int passes) {
+                                                                          uint32_t chunks, uint32_t start_stride_chunks,
+                                                                          int64_t total) {
   __shared__ __attribute__((aligned(1024))) uint8_t lds[kStreamLdsBytes];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t chunk = blockIdx.x % chunks;
-  const int64_t total = (int64_t)passes * chunks;
+  uint32_t chunk = (uint32_t)(((uint64_t)blockIdx.x * start_stride_chunks) % chunks);
   for (int64_t it = 0; it < total; ++it) {
     const uint8_t* src = region + (size_t)chunk * kStreamChunk + wave * 1024 + lane * 16;
     uint8_t* to = lds + ((it * kStreamChunk) % kStreamLdsBytes) + wave * 1024;
@@ -201,14 +201,15 @@ hinm_status hinm_calib_empty(void* stream) {
   return hipGetLastError() == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 
-hinm_status hinm_calib_lds_stream(const void* region, size_t region_bytes, int32_t passes, int32_t workgroups,
-                                  void* stream) {
+hinm_status hinm_calib_lds_stream(const void* region, size_t region_bytes, size_t start_stride_bytes,
+                                  int64_t chunks_per_workgroup, int32_t workgroups, void* stream) {
   if (!region) return HINM_ERR_NULL;
   if (region_bytes == 0 || region_bytes % kStreamChunk != 0 || region_bytes > ((size_t)1 << 40) || !aligned16(region) ||
-      passes <= 0 || workgroups <= 0)
+      start_stride_bytes % kStreamChunk != 0 || chunks_per_workgroup <= 0 || workgroups <= 0)
     return HINM_ERR_SHAPE;
   calib_lds_stream_kernel<<<(unsigned)workgroups, kStreamThreads, 0, static_cast<hipStream_t>(stream)>>>(
-      static_cast<const uint8_t*>(region), (uint32_t)(region_bytes / kStreamChunk), passes);
+      static_cast<const uint8_t*>(region), (uint32_t)(region_bytes / kStreamChunk),
+      (uint32_t)((start_stride_bytes / kStreamChunk) % (region_bytes / kStreamChunk)), chunks_per_workgroup);
   return hipGetLastError() == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 

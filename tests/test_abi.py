@@ -193,7 +193,8 @@ def test_calibration_entry_points_validate_before_launching():
     assert lib.hinm_calib_scatter_rows(fake, 64, 96, 96, None, 128, None) == 2    # row bytes not a multiple of the piece
     assert lib.hinm_calib_smfmac(5, 10, fake, None, None) == 3
     assert lib.hinm_calib_smfmac(0, 0, fake, None, None) == 2
-    assert lib.hinm_calib_lds_stream(fake, 1000, 1, 1, None) == 2
+    assert lib.hinm_calib_lds_stream(fake, 1000, 0, 1, 1, None) == 2
+    assert lib.hinm_calib_lds_stream(fake, 8192, 100, 1, 1, None) == 2
 
 
 def test_chain_validation():
