@@ -285,6 +285,32 @@ class CaseRun:
             wall, ev = (time.perf_counter() - t0) * 1e3, ev0.elapsed_time(ev1)
         return wall / steps, ev / steps
 
+    def tile_parts(self, steps):
+        """Where the layer's tile kernel spends its time: the same launch with only its copy stream, and with only
+        its LDS reads and MFMAs (hinm_calib_tile_part), each graph-timed over the rotated buffer sets.  None for a
+        workload that does not run on one tile-kernel launch per layer."""
+        if not self.use_prepared or self.variant or "spmm_tile_prepared_kernel" not in self.kernels \
+                or self.kernel_launches_per_step != self.n_layers:
+            return None
+        hinm, c, out = self.hinm, self.c, {}
+
+        def part(p):
+            def launch(i):
+                layers, X, _, _ = self.sets[i % self.n_sets]
+                hinm.hinm_calib_tile_part(c.M, c.K, c.V, c.Kv, c.dtype, self.N, layers[0][5], X, self.ldn, p)
+            return launch
+        try:
+            for p, name in ((1, "copy_stream_only_us"), (2, "lds_reads_and_mfma_only_us")):
+                part(p)(0)
+                self.torch.cuda.synchronize()
+                _, ev = graph_replay_ms(self.torch, part(p), steps)
+                out[name] = round(ev * 1e3 / steps, 2)
+        except RuntimeError:
+            return None
+        out["note"] = ("first layer's tile kernel launched with one side removed (nothing stored): which of the two "
+                       "the whole kernel's time follows says what bounds it")
+        return out
+
     def roofline(self, launch_ms, calib):
         """The dominant kernel against the roofline that bounds it: algorithmic bytes (or stored-value flops) of one
         launch over the average launch duration measured with HIP events over the timed region."""
@@ -461,6 +487,10 @@ def main():
     launch_ms = gpu_ms_per_step / run.launches_per_step
 
     roofline = run.roofline(launch_ms, calib)
+    if not args.no_calib:
+        parts = run.tile_parts(max(20, steps // 4))
+        if parts:
+            roofline["kernel_parts"] = parts
     if not args.columns:
         if live_traffic is not None:
             roofline["traffic"], roofline["traffic_source"] = live_traffic
@@ -538,6 +568,9 @@ def main():
                             "frac_calibrated": rf.get("frac_calibrated"), "kernel": rf["kernel"],
                             "layers_per_step": r.n_layers,
                             "dense_equiv_tflops": round(r.flops_dense_equiv / (g_ms * 1e-3) / 1e12, 1)}
+                parts = None if args.no_calib else r.tile_parts(max(20, k // 4))
+                if parts:
+                    per[key]["kernel_parts"] = {a: b for a, b in parts.items() if a != "note"}
                 r.free()
                 del r
             except Exception as err:   # one configuration failing must not lose the headline

@@ -61,6 +61,15 @@ hinm_status hinm_calib_empty(void* stream);
 hinm_status hinm_calib_lds_stream(const void* region, size_t region_bytes, size_t start_stride_bytes,
                                   int64_t chunks_per_workgroup, int32_t workgroups, void* stream);
 
+/* One part of the tile kernel that hinm_spmm_prepared would launch for this shape and N, on a real
+ * prepared layer (hinm_prepare) and a real X: part 1 = only its copy stream (gathered rows of X and the
+ * stored values through L2 into LDS, with the kernel's own barriers and waits; no LDS reads, no MFMAs),
+ * part 2 = only its LDS reads and MFMAs (no copies after the first stages, so the operands are stale).
+ * Nothing is stored.  For the shapes of the named workloads that run on the tile kernel in one launch
+ * (V of 64 or 128); HINM_ERR_UNSUPPORTED otherwise.  The two times say which side bounds the product. */
+hinm_status hinm_calib_tile_part(const hinm_shape* shape, int32_t N, const void* prepared, const void* X,
+                                 int64_t ldx, int32_t part, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

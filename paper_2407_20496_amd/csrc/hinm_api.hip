@@ -2,6 +2,7 @@
 // Every check here runs before anything is launched, so the error paths need no GPU.
 #include "hinm_internal.h"
 #include "prepared_layout.h"
+#include "hinm_calib.h"
 
 
 namespace {
@@ -534,6 +535,23 @@ hinm_status hinm_spmm_prepared_plan(const hinm_shape* shape, int32_t N, int64_t 
   st = run_prepared(shape, N, fake, fake, ldx, fake, ldy, flags, fake, ~size_t{0}, nullptr, &plan);
   if (launches) *launches = plan.launches;
   return st;
+}
+
+hinm_status hinm_calib_tile_part(const hinm_shape* shape, int32_t N, const void* prepared, const void* X, int64_t ldx,
+                                 int32_t part, void* stream) {
+  // Y is never written: any aligned non-NULL stand-in passes the checks
+  void* const no_y = reinterpret_cast<void*>(uintptr_t{1} << 20);
+  hinm_status st = check_prepared_call(shape, N, prepared, X, ldx, no_y, (N + 7) / 8 * 8, 0, nullptr, 0);
+  if (st != HINM_OK) return st;
+  if (part != 1 && part != 2) return HINM_ERR_UNSUPPORTED;
+  PreparedArgs a = prepared_args(shape, N, prepared, X, ldx, no_y, (N + 7) / 8 * 8, 0, nullptr, 0);
+  PreparedRoute route;
+  st = route_prepared(a, &route);
+  if (st != HINM_OK) return st;
+  if (route != PreparedRoute::Tile) return HINM_ERR_UNSUPPORTED;
+  hipError_t e = launch_spmm_tile_prepared_part(a, part, static_cast<hipStream_t>(stream));
+  if (e == hipErrorNotSupported) return HINM_ERR_UNSUPPORTED;
+  return e == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 
 const char* hinm_status_str(hinm_status s) {

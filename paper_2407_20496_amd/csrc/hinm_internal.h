@@ -226,6 +226,9 @@ struct PreparedArgs {
 };
 
 hipError_t launch_spmm_tile_prepared(const PreparedArgs& a, hipStream_t stream);
+// measurement aid: part 1 = only the copy stream of the tile kernel chosen for the shape, part 2 = only its LDS
+// reads and MFMAs; stores nothing; hipErrorNotSupported for shapes outside the named workloads' configurations
+hipError_t launch_spmm_tile_prepared_part(const PreparedArgs& a, int part, hipStream_t stream);
 // few input channels (a 64-column panel of X with all K rows fits in LDS): many tiles per workgroup
 bool spmm_panel_prepared_supported(const PreparedArgs& a);
 bool spmm_panel_prepared_preferred(const PreparedArgs& a);  // supported and faster than the tile kernel

@@ -58,7 +58,10 @@ struct TileCfg {
   static_assert(ST >= 2 && ST <= 4 && (A_INSTR + NW - 1) / NW <= 3, "wait table covers these");
 };
 
-template <int DT, int RB, int NB, int KSUB, int ST, int WC>
+// PART 0 is the product.  PART 1 and 2 are measurement aids (hinm_calib_tile_part): the same launch with only the
+// copy stream (no LDS reads, no MFMAs), or only the LDS reads and MFMAs (no copies after the prologue, so the
+// operands are whatever the first stages left in LDS); neither stores anything.
+template <int DT, int RB, int NB, int KSUB, int ST, int WC, int PART = 0>
 __global__ __launch_bounds__(NB / WC * 64) void spmm_tile_prepared_kernel(
     const uint8_t* __restrict__ prep_blocks, const int32_t* __restrict__ gather, const int32_t* __restrict__ out_rows,
     const uint8_t* __restrict__ zeros, const uint16_t* __restrict__ X, int64_t ldx, void* __restrict__ Y, int64_t ldy,
@@ -259,12 +262,16 @@ __global__ __launch_bounds__(NB / WC * 64) void spmm_tile_prepared_kernel(
     else wait_copies_outstanding<C::B_PER_WAVE>(later, extra_copies);
     __builtin_amdgcn_s_barrier();
     const int nxt = s + ST - 1;
-    if (nxt < stages_total) {
+    if (PART != 2 && nxt < stages_total) {
       issue_b(nxt, rows_next);
       issue_a(nxt);
     }
     rows_next = load_rows(nxt + 1);
-    compute_stage(s);
+    if constexpr (PART != 1) compute_stage(s);
+  }
+  if constexpr (PART != 0) {
+    // keeps the accumulators alive without ever storing them: no launch has a negative column count
+    if (N >= 0) return;
   }
 
   // ---- epilogue -------------------------------------------------------------------------------------
@@ -320,7 +327,7 @@ __global__ __launch_bounds__(NB / WC * 64) void spmm_tile_prepared_kernel(
 
 // Launches the tiles [tile_base, tile_base + tile_count) of the layer (tile_count < 0: all of them).  The kernel
 // numbers its tiles from zero: the tables it indexes by tile are handed over already advanced to tile_base.
-template <int DT, int RB, int NB, int KSUB, int ST, int WC = 64>
+template <int DT, int RB, int NB, int KSUB, int ST, int WC = 64, int PART = 0>
 hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream, int tile_base = 0, int tile_count = -1) {
   using C = TileCfg<RB, NB, KSUB, ST, WC>;
   const PreparedLayout L = prepared_layout(a.s);
@@ -328,10 +335,10 @@ hipError_t launch_cfg(const PreparedArgs& a, hipStream_t stream, int tile_base =
   const int n_blocks = (a.N + NB - 1) / NB;
   const int64_t work = (int64_t)n_blocks * T;
   const int work_per_xcd = (int)((work + 7) / 8);
-  constexpr auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST, WC>;
+  constexpr auto kernel = spmm_tile_prepared_kernel<DT, RB, NB, KSUB, ST, WC, PART>;
   if (a.plan) {
-    plan_record(a.plan, "spmm_tile_prepared_kernel<DT=%d,RB=%d,NB=%d,KSUB=%d,ST=%d,WC=%d> tiles=%d..%d grid=%d block=%d lds=%d",
-                DT, RB, NB, KSUB, ST, WC, tile_base, tile_base + T - 1, work_per_xcd * 8, C::THREADS, C::LDS_BYTES);
+    plan_record(a.plan, "spmm_tile_prepared_kernel<DT=%d,RB=%d,NB=%d,KSUB=%d,ST=%d,WC=%d%s> tiles=%d..%d grid=%d block=%d lds=%d",
+                DT, RB, NB, KSUB, ST, WC, PART == 1 ? ",copies only" : PART == 2 ? ",LDS reads and MFMAs only" : "", tile_base, tile_base + T - 1, work_per_xcd * 8, C::THREADS, C::LDS_BYTES);
     return hipSuccess;
   }
   if (hipError_t e = raise_lds_limit<kernel>(C::LDS_BYTES); e != hipSuccess) return e;
@@ -446,7 +453,37 @@ hipError_t launch_rb(const PreparedArgs& a, hipStream_t stream) {
   return launch_cfg<DT, RB, 256, 2, 3>(a, stream);
 }
 
+// One part of the kernel that launch_rb would choose for this shape, for the configurations the named
+// workloads use (tiles of 64 and 128 rows); anything else is refused.
+template <int DT, int RB, int PART>
+hipError_t launch_part_rb(const PreparedArgs& a, hipStream_t stream) {
+  switch (choose_variant(a)) {
+    case 3: return launch_cfg<DT, RB, 512, 2, 2, 64, PART>(a, stream);
+    case 16: return launch_cfg<DT, RB, 512, 2, 2, 32, PART>(a, stream);
+    case 14: return launch_cfg<DT, RB, 256, 2, 2, 32, PART>(a, stream);
+    case 17: return launch_cfg<DT, RB, 256, 1, 2, 32, PART>(a, stream);
+    case 13:
+      if constexpr (RB <= 2) return launch_cfg<DT, RB, 256, 4, 2, 32, PART>(a, stream);
+      break;
+    default: break;
+  }
+  return hipErrorNotSupported;
+}
+
 }  // namespace
+
+hipError_t launch_spmm_tile_prepared_part(const PreparedArgs& a, int part, hipStream_t stream) {
+  if ((a.s.V != 64 && a.s.V != 128) || (part != 1 && part != 2)) return hipErrorNotSupported;
+#define HINM_PART(DT)                                                                                   \
+  if (a.s.V == 64) return part == 1 ? launch_part_rb<DT, 2, 1>(a, stream) : launch_part_rb<DT, 2, 2>(a, stream); \
+  return part == 1 ? launch_part_rb<DT, 4, 1>(a, stream) : launch_part_rb<DT, 4, 2>(a, stream);
+  if (a.s.dtype == HINM_F16) {
+    HINM_PART(HINM_F16)
+  } else {
+    HINM_PART(HINM_BF16)
+  }
+#undef HINM_PART
+}
 
 hipError_t launch_spmm_tile_prepared(const PreparedArgs& a, hipStream_t stream) {
   const int RB = a.s.V / 32;

@@ -195,6 +195,14 @@ def test_calibration_entry_points_validate_before_launching():
     assert lib.hinm_calib_smfmac(0, 0, fake, None, None) == 2
     assert lib.hinm_calib_lds_stream(fake, 1000, 0, 1, 1, None) == 2
     assert lib.hinm_calib_lds_stream(fake, 8192, 100, 1, 1, None) == 2
+    # a part of the tile kernel: the same argument checks as the product, then only shapes that kernel serves
+    sh = binding._shape(256, 512, 64, 256, "bf16")
+    assert lib.hinm_calib_tile_part(C.byref(sh), 512, None, fake, 512, 1, None) == 1
+    assert lib.hinm_calib_tile_part(C.byref(sh), 512, fake, fake, 100, 1, None) == 2      # ldx below N
+    assert lib.hinm_calib_tile_part(C.byref(sh), 512, fake, fake, 512, 3, None) == 5      # no such part
+    sh16 = binding._shape(256, 512, 16, 256, "bf16")
+    assert lib.hinm_calib_tile_part(C.byref(sh16), 512, fake, fake, 512, 1, None) != 0    # no prepared form at V = 16
+    assert lib.hinm_calib_tile_part(C.byref(sh), 8, fake, fake, 8, 1, None) == 5          # few columns: another kernel
 
 
 def test_chain_validation():

@@ -272,3 +272,32 @@ def test_prepared_c3_decode_full(idx):
     c = synth.c3_cases()[idx]
     assert c.N in (1, 16)
     _check(c, c.N, [0])
+
+
+def test_tile_kernel_parts_run_and_store_nothing():
+    """The measurement launches (copy stream alone, LDS reads and MFMAs alone) finish, leave X and the prepared
+    layer as they were, and the product launched afterwards on the same buffers is still right."""
+    import torch
+    import paper_2407_20496_amd as hinm
+    from tests import gpu_util as gu
+    shapes = [(4096, 1024, 128, 512, 1100, "bf16"), (1024, 2048, 64, 1024, 1032, "f16")]   # both run on the tile kernel
+    for (M, K, V, Kv, N, dtype) in shapes:
+        ld = (N + 7) // 8 * 8
+        assert "spmm_tile_prepared_kernel" in hinm.hinm_spmm_prepared_plan(M, K, V, Kv, dtype, N, ld, ld, 0)[0]
+        case = synth.small_case(M, K, V, Kv, N, dtype, 77)
+        vals, nm, vec = orc.pack(case.weights(), case.dtype, V, Kv)
+        p = gu.upload_packed(M, K, V, Kv, dtype, vals, nm, vec)
+        pr = gu.gpu_prepare(p, case.pi_in(), case.pi_out())
+        prep = pr.buf
+        ld = (N + 7) // 8 * 8
+        Xh = np.zeros((K, ld), dtype=np.uint16)
+        Xh[:, :N] = case.activations(N)
+        X = torch.from_numpy(Xh.view(np.int16)).cuda()
+        before_x, before_p = X.clone(), prep.clone()
+        for part in (1, 2):
+            hinm.hinm_calib_tile_part(M, K, V, Kv, dtype, N, prep, X, ld, part)
+        torch.cuda.synchronize()
+        assert torch.equal(X, before_x) and torch.equal(prep, before_p)
+    with pytest.raises(hinm.HinmError):     # a shape served by another kernel has no tile-kernel parts
+        hinm.hinm_calib_tile_part(256, 512, 64, 256, "f16", 520, prep, X, 520, 1)
+    _check(synth.small_case(1024, 2048, 64, 1024, 1032, "f16", 77), 1032, [0])
