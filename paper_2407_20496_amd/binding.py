@@ -11,7 +11,8 @@ EPI_RELU, OUT_F32 = 1, 2
 KERNEL_REFERENCE, KERNEL_SMFMAC, KERNEL_GEMV = 0x100, 0x200, 0x400
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libhinm.so")
+# HINM_LIBRARY names another build of the same library (the host-sanitized one of build.py --sanitize)
+_LIB_PATH = os.environ.get("HINM_LIBRARY") or os.path.join(_HERE, "libhinm.so")
 _lib = None
 
 
