@@ -146,6 +146,17 @@ hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int3
                               void* vals, uint8_t* nm_idx, int32_t* vec_idx,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 3.2 (every arrangement of a tile's kept vectors is a valid layer; Section 4.2 searches over
+ * them): the order of all K input channels that makes hinm_pack_ordered / hinm_pack_scored /
+ * hinm_pack_vectors reproduce a given arrangement.  vec_idx is int32 [T][Kv] in device memory, row t
+ * the kept channels of tile t in some arrangement (as hinm_icp_search leaves them); tile_order,
+ * int32 [T][K] in device memory, receives for every tile those Kv channels in that arrangement
+ * followed by the remaining K - Kv channels in ascending order.  Rows of vec_idx are not checked:
+ * entries outside [0,K) are copied as they are, and a row with repeated or out-of-range entries
+ * gives a row of tile_order that is not a permutation (hinm_pack_ordered tolerates that).  K above
+ * 393216 returns HINM_ERR_UNSUPPORTED.  No workspace. */
+hinm_status hinm_tile_order(const hinm_shape* shape, const int32_t* vec_idx, int32_t* tile_order, void* stream);
+
 /* Section 4.1 (the saliency rho of Eq. 1-3; Section 5.1 names magnitude and second-order scores):
  * hinm_pack with caller-given scores.  rho is float32 [M][K] in device memory, one score per
  * weight, free of NaN.  Vector saliency = the sum of the V scores of the vector, accumulated in

@@ -163,6 +163,21 @@ def tile_order(vec_idx: np.ndarray, sigma: Optional[np.ndarray], K: int) -> np.n
     return out
 
 
+def order_from_arrangement(arrangement: np.ndarray, K: int) -> np.ndarray:
+    """The other direction of tile_order (Section 3.2: any arrangement of a tile's kept vectors is a valid
+    layer; Section 4.2 searches over them): an order of all K input channels per tile that reproduces a given
+    arrangement of the kept ones -- those Kv channels as arranged, then the pruned channels ascending."""
+    arrangement = np.asarray(arrangement)
+    T, Kv = arrangement.shape
+    out = np.empty((T, K), dtype=np.int32)
+    for t in range(T):
+        kept = arrangement[t].tolist()
+        assert len(set(kept)) == Kv and all(0 <= c < K for c in kept), "a row must name Kv distinct channels"
+        members = set(kept)
+        out[t] = kept + [c for c in range(K) if c not in members]
+    return out
+
+
 # --------------------------------------------------------------------------
 # Section 1 / Eq. 3 constraint: 2:4 selection on the surviving columns
 # --------------------------------------------------------------------------

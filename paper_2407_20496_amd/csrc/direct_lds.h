@@ -53,4 +53,50 @@ __device__ __forceinline__ void wait_copies_outstanding(int later, int extra) {
 // touches then sit on four different bank groups, for 16-lane as well as 32-lane LDS passes.
 __host__ __device__ constexpr int swizzle_of_row(int r) { return ((r & 3) << 1) | (((r >> 1) ^ r) & 1); }
 
+
+// One wave's share of the gathered input rows of a stage, copied straight into LDS as NB-column row segments.
+//   NB = 512: one wave-wide copy per row, lane = position of its 16 bytes in the 1024-byte segment;
+//   NB = 256: one copy per pair of consecutive rows, lanes 0..31 the even row, 32..63 the odd one.
+// A copy's source is a wave-uniform row base plus a per-lane byte offset that depends only on row % 4 (the
+// swizzle of swizzle_of_row, applied on the source side because a direct copy writes LDS linearly): the
+// offsets are computed once per kernel.  Lanes whose columns lie at or beyond N re-read the block's first
+// columns instead; the accumulator columns they feed are never stored.
+template <int NB>
+struct RowSegmentCopy {
+  static_assert(NB == 256 || NB == 512, "column block");
+  uint32_t off[4];            // by row % 4 (NB = 512)
+  uint32_t even_k, odd_k;     // NB = 256: this lane's offset in the k-th pair for even and odd k
+  int half;                   // NB = 256: which row of a pair this lane copies
+
+  __device__ __forceinline__ RowSegmentCopy(int lane, int n0, int N) {
+    const int gpos = (NB == 512) ? lane : (lane & 31);
+    half = (NB == 512) ? 0 : (lane >> 5);
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int granule = (((gpos >> 1) ^ swizzle_of_row(r4)) << 1) | (gpos & 1);  // which 16 bytes of the row segment
+      off[r4] = (n0 + granule * 8 < N) ? granule * 16 : 0;
+    }
+    // lane in half h copies row 2 k + h, so row % 4 is h for even k and 2 + h for odd k
+    even_k = half ? off[1] : off[0];
+    odd_k = half ? off[3] : off[2];
+  }
+
+  // Issues COPIES wave-wide copies: rows j = 0 .. of this wave (row_base(j) = wave-uniform source address of the
+  // wave's j-th row at the block's first column) land at first_row + j * ROW_BYTES.  The wave's first row must
+  // have an index that is a multiple of four in the stage (it has: waves own 4, 8 or 16 consecutive rows).
+  template <int COPIES, int ROW_BYTES, class RowBase>
+  __device__ __forceinline__ void issue(RowBase row_base, uint8_t* first_row) const {
+#pragma unroll
+    for (int k = 0; k < COPIES; ++k) {
+      if constexpr (NB == 512) {
+        copy16_to_lds(row_base(k) + off[k & 3], first_row + k * ROW_BYTES);
+      } else {
+        const uint8_t* be = row_base(2 * k);
+        const uint8_t* bo = row_base(2 * k + 1);
+        copy16_to_lds((half ? bo : be) + ((k & 1) ? odd_k : even_k), first_row + 2 * k * ROW_BYTES);
+      }
+    }
+  }
+};
+
 }  // namespace hinm

@@ -162,6 +162,16 @@ hinm_status hinm_pack_vectors(const hinm_shape* shape, const void* W, const floa
                   workspace_bytes, stream);
 }
 
+hinm_status hinm_tile_order(const hinm_shape* shape, const int32_t* vec_idx, int32_t* tile_order, void* stream) {
+  hinm_status st = check_shape(shape);
+  if (st != HINM_OK) return st;
+  if (!vec_idx || !tile_order) return HINM_ERR_NULL;
+  if (!aligned(vec_idx, 4) || !aligned(tile_order, 4)) return HINM_ERR_SHAPE;
+  if (shape->K > kPackOrderMaxK) return HINM_ERR_UNSUPPORTED;
+  return launch_tile_order(*shape, vec_idx, tile_order, static_cast<hipStream_t>(stream)) == hipSuccess ? HINM_OK
+                                                                                                          : HINM_ERR_DEVICE;
+}
+
 static hinm_status check_icp_shape(const hinm_shape* shape) {
   hinm_status st = check_shape(shape);
   if (st != HINM_OK) return st;

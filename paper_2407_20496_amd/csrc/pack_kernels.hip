@@ -575,7 +575,57 @@ __global__ __launch_bounds__(kOrderThreads) void order_kernel(const int32_t* __r
   }
 }
 
+// The inverse bookkeeping (Section 3.2: any arrangement of a tile's kept vectors is a valid layer): from an
+// arrangement vec_idx[t][0..Kv) to a full order of the K input channels that reproduces it when given to
+// order_kernel: the kept channels in their arrangement, then the pruned ones ascending.  One workgroup per
+// tile: bitmap of the kept channels in LDS, then one ordered sweep over the channels with workgroup prefix sums.
+// Entries of vec_idx outside [0, K) are copied but mark nothing; nothing is written past slot K - 1.
+__global__ __launch_bounds__(kOrderThreads) void tile_order_kernel(const int32_t* __restrict__ vec_idx,
+                                                                   int32_t* __restrict__ sigma, int K, int Kv) {
+  extern __shared__ uint32_t kept_bits[];  // ceil(K / 32) words
+  __shared__ uint32_t wave_count[kOrderThreads / 64];
+  const int t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int32_t* vi = vec_idx + (size_t)t * Kv;
+  int32_t* sg = sigma + (size_t)t * K;
+  for (int w = tid; w < (K + 31) / 32; w += kOrderThreads) kept_bits[w] = 0;
+  __syncthreads();
+  for (int j = tid; j < Kv; j += kOrderThreads) {
+    const int c = vi[j];
+    sg[j] = c;
+    if (c >= 0 && c < K) atomicOr(&kept_bits[c >> 5], 1u << (c & 31));
+  }
+  __syncthreads();
+  int done = Kv;  // slots written so far (same value in every thread)
+  for (int base = 0; base < K; base += kOrderThreads) {
+    const int c = base + tid;
+    const bool take = c < K && !((kept_bits[c >> 5] >> (c & 31)) & 1u);
+    const uint64_t votes = __ballot(take);
+    const int before_in_wave = __popcll(votes & ((1ull << lane) - 1));
+    if (lane == 0) wave_count[wave] = (uint32_t)__popcll(votes);
+    __syncthreads();
+    int before_waves = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kOrderThreads / 64; ++w) {
+      const int n = (int)wave_count[w];
+      if (w < wave) before_waves += n;
+      total += n;
+    }
+    const int pos = done + before_waves + before_in_wave;
+    if (take && pos < K) sg[pos] = c;
+    done += total;
+    __syncthreads();  // wave_count is rewritten by the next sweep
+  }
+}
+
 }  // namespace
+
+hipError_t launch_tile_order(const hinm_shape& s, const int32_t* vec_idx, int32_t* tile_order, hipStream_t stream) {
+  tile_order_kernel<<<s.M / s.V, kOrderThreads, (size_t)((s.K + 31) / 32) * 4, stream>>>(vec_idx, tile_order, s.K, s.Kv);
+  return hipGetLastError();
+}
 
 hipError_t launch_pack(const PackArgs& a, hipStream_t stream) {
   const hinm_shape& s = a.s;

@@ -16,6 +16,7 @@
 #include "hinm_internal.h"
 #include "mfma_types.h"
 #include "direct_lds.h"
+#include "tile_epilogue.h"
 
 #include <type_traits>
 
@@ -238,54 +239,8 @@ __global__ __launch_bounds__(kThreads) void spmm_tile_kernel(
   }
 
   // ---- epilogue -----------------------------------------------------------------------------------
-  // D layout: lane holds column lane % 32, rows 8 * (reg / 4) + 4 * (lane / 32) + reg % 4.
-  if (out_f32) {
-    float* Yf = static_cast<float*>(Y);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int r = t * V + 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
-        const int64_t out_row = pi_out ? pi_out[r] : r;
-#pragma unroll
-        for (int cb = 0; cb < kCB; ++cb) {
-          const int n = n0 + wave * 64 + cb * 32 + i32;
-          float v = acc[rb][cb][e];
-          if (relu) v = v > 0.f ? v : 0.f;
-          if (n < N) Yf[out_row * ldy + n] = v;
-        }
-      }
-    return;
-  }
-  // the last loop iteration ended with a barrier: both stages are free
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int cb = 0; cb < kCB; ++cb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
-        const int col = wave * 64 + cb * 32 + i32;
-        float v = acc[rb][cb][e];
-        if (relu) v = v > 0.f ? v : 0.f;
-        *reinterpret_cast<uint16_t*>(lds + row * kYStride + col * 2) = float_to_bits<DT>(v);
-      }
-  __syncthreads();
-  uint16_t* Yh = static_cast<uint16_t*>(Y);
-  // 32 lanes move one 512-byte row; a wave moves two rows per pass
-  for (int row = (tid >> 5); row < V; row += kThreads / 32) {
-    const int r = t * V + row;
-    const int64_t out_row = pi_out ? pi_out[r] : r;
-    const int n = n0 + b_chunk * 8;
-    const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * kYStride + b_chunk * 16);
-    uint16_t* dst = Yh + out_row * ldy + n;
-    if (n + 8 <= N) {
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
-    } else if (n < N) {
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-      for (int e = 0; e < N - n; ++e) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-    }
-  }
+  store_tile_rows<DT, RB, kCB, kNB, 64, kThreads, kYStride>(acc, lds, Y, ldy, N, n0, relu, out_f32,
+                                                            [&](int row) -> int64_t { const int r = t * V + row; return pi_out ? pi_out[r] : r; });
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -358,16 +313,7 @@ __global__ __launch_bounds__(NB / WC * 64) void spmm_tile_dma_kernel(
   const uint8_t* nm_tile = nm_idx + (size_t)t * V * (Kv / 8);
 
   // ---- copy roles (B as in the sparse tile kernel) -------------------------------------------------
-  const int gpos = (NB == 512) ? lane : (lane & 31);
-  const int half = (NB == 512) ? 0 : (lane >> 5);
-  uint32_t b_src_off[4];
-#pragma unroll
-  for (int r4 = 0; r4 < 4; ++r4) {
-    const int granule = (((gpos >> 1) ^ swizzle_of_row(r4)) << 1) | (gpos & 1);  // which 16 bytes of the row segment
-    b_src_off[r4] = (n0 + granule * 8 < N) ? granule * 16 : 0;  // columns beyond N re-read the first ones, never stored
-  }
-  const uint32_t b_off_even_k = half ? b_src_off[1] : b_src_off[0];
-  const uint32_t b_off_odd_k = half ? b_src_off[3] : b_src_off[2];
+  const RowSegmentCopy<NB> b_copy(lane, n0, N);
   // A values: wave-wide copy number i moves rows 16 i .. 16 i + 15; lane l lands at 16 l = row 16 i + l / 4,
   // chunk position l % 4, and fetches chunk (l % 4) ^ ((row / 4) % 4) of that row's 64 bytes.
   // A nibbles: copy number k moves dwords 64 k .. 64 k + 63 of the stage's [substep][row] array.
@@ -404,17 +350,8 @@ __global__ __launch_bounds__(NB / WC * 64) void spmm_tile_dma_kernel(
   auto a_buffer = [&](int stage_idx) -> uint8_t* { return lds + (stage_idx & 1) * C::STAGE_BYTES + C::B_BYTES; };
   auto issue_stage = [&](int stage_idx, const rows_t rows) {
     uint8_t* bs = b_buffer(stage_idx);
-#pragma unroll
-    for (int k = 0; k < C::B_PER_WAVE; ++k) {
-      if constexpr (NB == 512) {
-        copy16_to_lds(row_base(rows[k]) + b_src_off[k & 3], bs + (wave * RPW + k) * C::ROW_BYTES);
-      } else {
-        const uint8_t* be = row_base(rows[2 * k]);
-        const uint8_t* bo = row_base(rows[2 * k + 1]);
-        const uint8_t* src = (half ? bo : be) + ((k & 1) ? b_off_odd_k : b_off_even_k);
-        copy16_to_lds(src, bs + (wave * RPW + 2 * k) * C::ROW_BYTES);
-      }
-    }
+    b_copy.template issue<C::B_PER_WAVE, C::ROW_BYTES>([&](int j) { return row_base(rows[j]); },
+                                                        bs + wave * RPW * C::ROW_BYTES);
     uint8_t* as = a_buffer(stage_idx);
 #pragma unroll
     for (int m = 0; m < C::A_ROUNDS; ++m) {
@@ -504,54 +441,8 @@ __global__ __launch_bounds__(NB / WC * 64) void spmm_tile_dma_kernel(
   }
 
   // ---- epilogue -------------------------------------------------------------------------------------------
-  if (out_f32) {
-    float* Yf = static_cast<float*>(Y);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int r = t * V + 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
-        const int64_t out_row = pi_out ? pi_out[r] : r;
-#pragma unroll
-        for (int cb = 0; cb < CBS; ++cb) {
-          const int n = n0 + wave * WC + cb * 32 + i32;
-          float v = acc[rb][cb][e];
-          if (relu) v = v > 0.f ? v : 0.f;
-          if (n < N) Yf[out_row * ldy + n] = v;
-        }
-      }
-    return;
-  }
-  __builtin_amdgcn_s_barrier();  // every wave is done reading the stages
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int cb = 0; cb < CBS; ++cb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = 32 * rb + 8 * (e >> 2) + 4 * qh + (e & 3);
-        const int col = wave * WC + cb * 32 + i32;
-        float v = acc[rb][cb][e];
-        if (relu) v = v > 0.f ? v : 0.f;
-        *reinterpret_cast<uint16_t*>(lds + row * C::Y_STRIDE + col * 2) = float_to_bits<DT>(v);
-      }
-  __syncthreads();
-  uint16_t* Yh = static_cast<uint16_t*>(Y);
-  constexpr int LANES_PER_ROW = NB / 8;
-  const int chunk = tid % LANES_PER_ROW;
-  for (int row = tid / LANES_PER_ROW; row < V; row += C::THREADS / LANES_PER_ROW) {
-    const int r = t * V + row;
-    const int64_t out_row = pi_out ? pi_out[r] : r;
-    const int n = n0 + chunk * 8;
-    const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * C::Y_STRIDE + chunk * 16);
-    uint16_t* dst = Yh + out_row * ldy + n;
-    if (n + 8 <= N) {
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
-    } else if (n < N) {
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-      for (int e = 0; e < N - n; ++e) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-    }
-  }
+  store_tile_rows<DT, RB, CBS, NB, WC, C::THREADS, C::Y_STRIDE>(acc, lds, Y, ldy, N, n0, relu, out_f32,
+                                                                  [&](int row) -> int64_t { const int r = t * V + row; return pi_out ? pi_out[r] : r; });
 }
 
 template <int DT, int RB, int KSUB>

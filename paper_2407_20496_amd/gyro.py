@@ -1,7 +1,7 @@
 """Host-side driver of the permutation search (arXiv 2407.20496, Section 4.2) over the C-ABI entry points.
 
 Everything the method computes runs in the library's kernels (hinm_ocp_cluster, hinm_ocp_search,
-hinm_pack_vectors, hinm_icp_search, hinm_pack_ordered / hinm_pack_scored).  This module only does what the
+hinm_pack_vectors, hinm_icp_search, hinm_tile_order, hinm_pack_ordered / hinm_pack_scored).  This module only does what the
 paper leaves to the caller: it draws the samples of every iteration from a seeded generator, decides how many
 channels are sampled per iteration, and moves index arrays between the calls.  PyTorch is used for device
 memory and for re-ordering rows by an index tensor.
@@ -24,16 +24,6 @@ def default_sample_schedule(V: int, iters: int) -> Sequence[int]:
     top = max(1, V // 8)
     levels = int(np.log2(top)) + 1
     return [max(1, top >> min(levels - 1, (i * levels) // iters)) for i in range(iters)]
-
-
-def tile_order_from_vec_idx(vec_idx: torch.Tensor, K: int) -> torch.Tensor:
-    """int32 [T][K]: every tile's kept channels in the given arrangement, then the pruned ones ascending -- the
-    `tile_order` argument that makes hinm_pack_ordered / hinm_pack_scored reproduce the arrangement."""
-    T, Kv = vec_idx.shape
-    key = torch.arange(K, device=vec_idx.device, dtype=torch.int64).repeat(T, 1) + Kv      # pruned: Kv + channel
-    pos = torch.arange(Kv, device=vec_idx.device, dtype=torch.int64).repeat(T, 1)
-    key.scatter_(1, vec_idx.to(torch.int64), pos)                                          # kept: position
-    return torch.argsort(key, dim=1).to(torch.int32).contiguous()
 
 
 def gyro_permute(W: torch.Tensor, V: int, Kv: int, dtype, rho: Optional[torch.Tensor] = None, ocp_iters: int = 8,
@@ -86,7 +76,8 @@ def gyro_permute(W: torch.Tensor, V: int, Kv: int, dtype, rho: Optional[torch.Te
         ws2 = torch.empty(wsb, dtype=torch.uint8, device=dev)
         icp_trace = torch.zeros((icp_iters, T), dtype=torch.float64, device=dev)
         hb.hinm_icp_search(M, K, V, Kv, dtype, Wp, rho_p, vec_idx, samples, icp_iters, icp_trace, ws2, wsb)
-    sigma = tile_order_from_vec_idx(vec_idx, K)
+    sigma = torch.empty((T, K), dtype=torch.int32, device=dev)
+    hb.hinm_tile_order(M, K, V, Kv, dtype, vec_idx, sigma)
     vals = torch.empty(vb // 2, dtype=torch.int16, device=dev)
     nm_idx = torch.empty(nb, dtype=torch.uint8, device=dev)
     vec_out = torch.empty((T, Kv), dtype=torch.int32, device=dev)

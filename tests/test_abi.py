@@ -205,6 +205,18 @@ def test_calibration_entry_points_validate_before_launching():
     assert lib.hinm_calib_tile_part(C.byref(sh), 8, fake, fake, 8, 1, None) == 5          # few columns: another kernel
 
 
+def test_tile_order_validation():
+    lib = hinm.load_library()
+    fake = 0x1000
+    sh = binding._shape(64, 96, 16, 48, "f16")
+    assert lib.hinm_tile_order(C.byref(sh), None, fake, None) == 1
+    assert lib.hinm_tile_order(C.byref(sh), fake, None, None) == 1
+    assert lib.hinm_tile_order(C.byref(sh), fake + 2, fake, None) == 2
+    assert lib.hinm_tile_order(C.byref(binding._shape(64, 96, 16, 50, "f16")), fake, fake, None) == 2   # Kv % 8
+    big = binding._shape(16, 400000, 16, 48, "f16")
+    assert lib.hinm_tile_order(C.byref(big), fake, fake, None) == 5
+
+
 def test_chain_validation():
     lib = hinm.load_library()
     fake = 0x1000

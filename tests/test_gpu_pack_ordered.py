@@ -111,3 +111,37 @@ def test_products_follow_an_unordered_vector_index(M, K, V, Kv, N, dtype):
         pr = gu.gpu_prepare(p, pin, pout)
         got = gu.gpu_spmm_prepared(pr, Xb, 2).astype(np.float64)
         gu.check_close(got, want, what="prepared kernels, ordered vector index")
+
+
+@pytest.mark.parametrize("T,K,Kv", [(4, 96, 48), (3, 1000, 504), (2, 4096, 1024), (1, 5000, 4096), (2, 16, 16),
+                                     (5, 11008, 5504)])
+def test_tile_order_from_an_arrangement(T, K, Kv):
+    """hinm_tile_order: kept channels as arranged, then the pruned ones ascending, bit for bit; and the order it
+    returns makes hinm_pack_ordered reproduce the arrangement."""
+    import torch
+    import paper_2407_20496_amd as hinm
+    rng = np.random.default_rng(K + Kv)
+    arr = np.stack([rng.permutation(K)[:Kv] for _ in range(T)]).astype(np.int32)
+    want = orc.order_from_arrangement(arr, K)
+    vec = torch.from_numpy(arr).cuda()
+    out = torch.full((T, K), -7, dtype=torch.int32, device="cuda")
+    hinm.hinm_tile_order(T * 4, K, 4, Kv, "f16", vec, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+def test_tile_order_round_trip_through_pack_ordered():
+    from tests import gpu_util as gu
+    import torch
+    import paper_2407_20496_amd as hinm
+    c = synth.small_case(128, 1000, 32, 504, 4, "bf16", 33)
+    Wb = c.weights()
+    plain = gu.gpu_pack(Wb, c.dtype, c.V, c.Kv)
+    kept = plain.host()[2]
+    rng = np.random.default_rng(9)
+    arr = np.stack([rng.permutation(kept[t]) for t in range(c.T)]).astype(np.int32)
+    sigma = torch.empty((c.T, c.K), dtype=torch.int32, device="cuda")
+    hinm.hinm_tile_order(c.M, c.K, c.V, c.Kv, c.dtype, torch.from_numpy(arr).cuda(), sigma)
+    torch.cuda.synchronize()
+    again = gu.gpu_pack(Wb, c.dtype, c.V, c.Kv, sigma=sigma.cpu().numpy()).host()[2]
+    assert np.array_equal(again, arr)

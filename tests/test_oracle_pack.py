@@ -136,6 +136,23 @@ def test_tile_order_keeps_the_vector_mask_and_regroups(dtype):
 
 # ---- caller-given saliency rho (Section 4.1, Eq. 1-3; Section 5.1) and the vector-only state (Section 5.1.2) ----
 
+def test_order_from_arrangement_by_hand_and_round_trip():
+    # by hand: K = 6, tile keeps channels 4, 1, 3 in that arrangement -> 4 1 3 then the others ascending 0 2 5
+    assert orc.order_from_arrangement(np.array([[4, 1, 3]]), 6).tolist() == [[4, 1, 3, 0, 2, 5]]
+    assert orc.order_from_arrangement(np.array([[0, 1]]), 2).tolist() == [[0, 1]]          # everything kept
+    # round trip through tile_order (pinned by the hand example above): the order reproduces the arrangement
+    rng = np.random.default_rng(5)
+    T, K, Kv = 3, 40, 12
+    kept = np.stack([np.sort(rng.permutation(K)[:Kv]) for _ in range(T)])
+    arr = np.stack([rng.permutation(kept[t]) for t in range(T)])
+    sigma = orc.order_from_arrangement(arr, K)
+    assert all(sorted(sigma[t].tolist()) == list(range(K)) for t in range(T))
+    assert np.array_equal(orc.tile_order(kept, sigma, K), arr)
+    assert all(np.all(np.diff(sigma[t, Kv:]) > 0) for t in range(T))                      # pruned ones ascending
+    with pytest.raises(AssertionError):
+        orc.order_from_arrangement(np.array([[1, 1, 2]]), 6)
+
+
 def test_hand_example_with_scores(hand_example):
     from tests.conftest import load_golden
     ex, sc = hand_example, load_golden("hand_example_v4_scores.txt")
