@@ -146,6 +146,15 @@ hinm_status hinm_pack_ordered(const hinm_shape* shape, const void* W, const int3
                               void* vals, uint8_t* nm_idx, int32_t* vec_idx,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 4.2 (the output-channel search ends in an order of the output channels; Section 3.2: that
+ * order is applied offline, to the rows of the weight matrix, before the layer is packed):
+ * dst row r = src row row_order[r], for matrices of `rows` rows of row_bytes bytes each (the weights,
+ * and a caller's saliency matrix alike; row_bytes a multiple of 4), all in device memory, src and dst
+ * distinct and not overlapping.  row_order is int32 [rows]; it is not checked for being a
+ * permutation: a destination row whose entry is outside [0, rows) is left unwritten. */
+hinm_status hinm_apply_row_order(const void* src, void* dst, const int32_t* row_order, int32_t rows,
+                                 size_t row_bytes, void* stream);
+
 /* Section 3.2 (every arrangement of a tile's kept vectors is a valid layer; Section 4.2 searches over
  * them): the order of all K input channels that makes hinm_pack_ordered / hinm_pack_scored /
  * hinm_pack_vectors reproduce a given arrangement.  vec_idx is int32 [T][Kv] in device memory, row t

@@ -13,7 +13,7 @@ from __future__ import annotations
 from .binding import (  # noqa: F401
     F16, BF16, EPI_RELU, OUT_F32, KERNEL_REFERENCE, KERNEL_SMFMAC, KERNEL_GEMV,
     HinmError, Layer, library_path, load_library, exported_symbols,
-    hinm_pack_sizes, hinm_pack, hinm_pack_static, PACK_STATIC_MAX_SCORES, hinm_pack_ordered, hinm_tile_order, hinm_pack_scored, hinm_pack_vectors, hinm_unpack, hinm_spmm,
+    hinm_pack_sizes, hinm_pack, hinm_pack_static, PACK_STATIC_MAX_SCORES, hinm_pack_ordered, hinm_tile_order, hinm_apply_row_order, hinm_pack_scored, hinm_pack_vectors, hinm_unpack, hinm_spmm,
     hinm_spmm_vectors, hinm_icp_sizes, hinm_icp_search, hinm_ocp_sizes, hinm_ocp_search, hinm_ocp_cluster_sizes, hinm_ocp_cluster,
     hinm_chain_sizes, hinm_chain,
     hinm_prepare_sizes, hinm_prepare, hinm_spmm_prepared_workspace, hinm_spmm_prepared, hinm_spmm_prepared_plan,

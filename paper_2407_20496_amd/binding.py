@@ -37,7 +37,7 @@ def library_path() -> str:
 
 def exported_symbols() -> Tuple[str, ...]:
     """Entry points include/hinm.h declares."""
-    return ("hinm_pack_sizes", "hinm_pack", "hinm_pack_static", "hinm_pack_ordered", "hinm_tile_order", "hinm_pack_scored", "hinm_pack_vectors",
+    return ("hinm_pack_sizes", "hinm_pack", "hinm_pack_static", "hinm_pack_ordered", "hinm_tile_order", "hinm_apply_row_order", "hinm_pack_scored", "hinm_pack_vectors",
             "hinm_icp_sizes", "hinm_icp_search", "hinm_ocp_sizes", "hinm_ocp_search",
             "hinm_ocp_cluster_sizes", "hinm_ocp_cluster", "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_prepare_sizes", "hinm_prepare",
             "hinm_spmm_prepared_workspace", "hinm_spmm_prepared", "hinm_spmm_prepared_plan", "hinm_chain_sizes",
@@ -70,6 +70,7 @@ def load_library():
     lib.hinm_pack.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.hinm_pack_static.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.hinm_tile_order.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.hinm_apply_row_order.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_size_t, C.c_void_p]
     lib.hinm_pack_ordered.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
     lib.hinm_pack_scored.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -103,7 +104,7 @@ def load_library():
     lib.hinm_spmm_prepared_plan.argtypes = [sp, C.c_int32, C.c_int64, C.c_int64, C.c_uint32, C.c_char_p, C.c_size_t,
                                             C.POINTER(C.c_int32)]
     lib.hinm_spmm_prepared_plan.restype = C.c_int
-    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_pack_static", "hinm_pack_ordered", "hinm_tile_order", "hinm_pack_scored", "hinm_pack_vectors",
+    for name in ("hinm_pack_sizes", "hinm_pack", "hinm_pack_static", "hinm_pack_ordered", "hinm_tile_order", "hinm_apply_row_order", "hinm_pack_scored", "hinm_pack_vectors",
                  "hinm_icp_sizes", "hinm_icp_search", "hinm_ocp_sizes", "hinm_ocp_search",
                  "hinm_ocp_cluster_sizes", "hinm_ocp_cluster", "hinm_unpack", "hinm_spmm", "hinm_spmm_vectors", "hinm_chain_sizes", "hinm_chain",
                  "hinm_prepare_sizes", "hinm_prepare", "hinm_spmm_prepared_workspace", "hinm_spmm_prepared"):
@@ -201,6 +202,11 @@ def hinm_pack_static(M, K, V, Kv, dtype, W, vals, nm_idx, vec_idx, stream=None) 
     lib = load_library()
     _check(lib.hinm_pack_static(C.byref(_shape(M, K, V, Kv, dtype)), _ptr(W), _ptr(vals), _ptr(nm_idx), _ptr(vec_idx),
                                 _stream(stream)), "hinm_pack_static")
+
+
+def hinm_apply_row_order(src, dst, row_order, rows, row_bytes, stream=None) -> None:
+    _check(load_library().hinm_apply_row_order(_ptr(src), _ptr(dst), _ptr(row_order), int(rows), int(row_bytes),
+                                               _stream(stream)), "hinm_apply_row_order")
 
 
 def hinm_tile_order(M, K, V, Kv, dtype, vec_idx, tile_order, stream=None) -> None:

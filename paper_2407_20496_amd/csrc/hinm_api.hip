@@ -162,6 +162,17 @@ hinm_status hinm_pack_vectors(const hinm_shape* shape, const void* W, const floa
                   workspace_bytes, stream);
 }
 
+hinm_status hinm_apply_row_order(const void* src, void* dst, const int32_t* row_order, int32_t rows, size_t row_bytes,
+                                 void* stream) {
+  if (!src || !dst || !row_order) return HINM_ERR_NULL;
+  if (rows <= 0 || row_bytes == 0 || row_bytes % 4 != 0 || !aligned(src, 4) || !aligned(dst, 4) || !aligned(row_order, 4) ||
+      src == dst)
+    return HINM_ERR_SHAPE;
+  return launch_gather_rows(src, dst, row_order, rows, row_bytes, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? HINM_OK
+             : HINM_ERR_DEVICE;
+}
+
 hinm_status hinm_tile_order(const hinm_shape* shape, const int32_t* vec_idx, int32_t* tile_order, void* stream) {
   hinm_status st = check_shape(shape);
   if (st != HINM_OK) return st;

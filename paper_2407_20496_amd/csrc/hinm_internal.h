@@ -90,6 +90,9 @@ struct PackArgs {
   double* scores;             // workspace, [T][K]
 };
 hipError_t launch_pack(const PackArgs& a, hipStream_t stream);
+// dst row r = src row row_order[r] (rows of row_bytes bytes, a multiple of 4)
+hipError_t launch_gather_rows(const void* src, void* dst, const int32_t* row_order, int rows, size_t row_bytes,
+                              hipStream_t stream);
 // vec_idx [T][Kv] (an arrangement of every tile's kept channels) -> tile_order [T][K] that reproduces it
 hipError_t launch_tile_order(const hinm_shape& s, const int32_t* vec_idx, int32_t* tile_order, hipStream_t stream);
 constexpr int kPackOrderMaxK = 32 * 12 * 1024;  // the bitmap of kept columns must fit 48 KB of LDS

@@ -620,7 +620,27 @@ __global__ __launch_bounds__(kOrderThreads) void tile_order_kernel(const int32_t
   }
 }
 
+// dst row r = src row row_order[r]; rows of row_bytes bytes (a multiple of 4), one workgroup per row.  Rows named
+// outside [0, rows) are left unwritten.
+__global__ __launch_bounds__(256) void gather_rows_by_order_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst,
+                                                                   const int32_t* __restrict__ row_order, int rows,
+                                                                   size_t row_words) {
+  const int r = blockIdx.x;
+  const int from = row_order[r];
+  if (from < 0 || from >= rows) return;
+  const uint32_t* in = src + (size_t)from * row_words;
+  uint32_t* out = dst + (size_t)r * row_words;
+  for (size_t i = threadIdx.x; i < row_words; i += 256) out[i] = in[i];
+}
+
 }  // namespace
+
+hipError_t launch_gather_rows(const void* src, void* dst, const int32_t* row_order, int rows, size_t row_bytes,
+                              hipStream_t stream) {
+  gather_rows_by_order_kernel<<<rows, 256, 0, stream>>>(static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst),
+                                                         row_order, rows, row_bytes / 4);
+  return hipGetLastError();
+}
 
 hipError_t launch_tile_order(const hinm_shape& s, const int32_t* vec_idx, int32_t* tile_order, hipStream_t stream) {
   tile_order_kernel<<<s.M / s.V, kOrderThreads, (size_t)((s.K + 31) / 32) * 4, stream>>>(vec_idx, tile_order, s.K, s.Kv);

@@ -3,8 +3,8 @@
 Everything the method computes runs in the library's kernels (hinm_ocp_cluster, hinm_ocp_search,
 hinm_pack_vectors, hinm_icp_search, hinm_tile_order, hinm_pack_ordered / hinm_pack_scored).  This module only does what the
 paper leaves to the caller: it draws the samples of every iteration from a seeded generator, decides how many
-channels are sampled per iteration, and moves index arrays between the calls.  PyTorch is used for device
-memory and for re-ordering rows by an index tensor.
+channels are sampled per iteration, and hands arrays from one call to the next.  PyTorch is used for device
+memory only.
 """
 from __future__ import annotations
 
@@ -60,9 +60,13 @@ def gyro_permute(W: torch.Tensor, V: int, Kv: int, dtype, rho: Optional[torch.Te
         hb.hinm_ocp_search(M, K, V, Kv, dtype, Wb, rho, row_order, samples, clusters, n, 1, obj, ws, wsb)
         ocp_trace.append(obj)
     # the layer with its rows in the order found
-    idx = row_order.to(torch.int64)
-    Wp = Wb.index_select(0, idx).contiguous()
-    rho_p = None if rho is None else rho.index_select(0, idx).contiguous()
+    Wp = torch.empty_like(Wb)
+    hb.hinm_apply_row_order(Wb, Wp, row_order, M, K * 2)
+    rho_p = None
+    if rho is not None:
+        rho_c = rho.contiguous()
+        rho_p = torch.empty((M, K), dtype=rho.dtype, device=dev)
+        hb.hinm_apply_row_order(rho_c, rho_p, row_order, M, K * 4)
     vb, nb, cb, wb = hb.hinm_pack_sizes(M, K, V, Kv, dtype)
     ws = torch.empty(wb // 8, dtype=torch.float64, device=dev)
     vals_v = torch.empty(M * Kv, dtype=torch.int16, device=dev)

@@ -205,6 +205,16 @@ def test_calibration_entry_points_validate_before_launching():
     assert lib.hinm_calib_tile_part(C.byref(sh), 8, fake, fake, 8, 1, None) == 5          # few columns: another kernel
 
 
+def test_apply_row_order_validation():
+    lib = hinm.load_library()
+    fake = 0x1000
+    assert lib.hinm_apply_row_order(None, fake + 4096, fake, 4, 64, None) == 1
+    assert lib.hinm_apply_row_order(fake, fake + 4096, None, 4, 64, None) == 1
+    assert lib.hinm_apply_row_order(fake, fake, fake + 8192, 4, 64, None) == 2           # in place
+    assert lib.hinm_apply_row_order(fake, fake + 4096, fake + 8192, 4, 66, None) == 2    # row bytes not a multiple of 4
+    assert lib.hinm_apply_row_order(fake, fake + 4096, fake + 8192, 0, 64, None) == 2
+
+
 def test_tile_order_validation():
     lib = hinm.load_library()
     fake = 0x1000

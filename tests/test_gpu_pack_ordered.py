@@ -145,3 +145,17 @@ def test_tile_order_round_trip_through_pack_ordered():
     torch.cuda.synchronize()
     again = gu.gpu_pack(Wb, c.dtype, c.V, c.Kv, sigma=sigma.cpu().numpy()).host()[2]
     assert np.array_equal(again, arr)
+
+
+def test_apply_row_order_is_a_row_gather():
+    import torch
+    import paper_2407_20496_amd as hinm
+    rng = np.random.default_rng(3)
+    for rows, row_bytes in ((37, 4), (256, 2000), (1000, 8192 * 2)):
+        src = rng.integers(0, 256, size=(rows, row_bytes), dtype=np.uint8)
+        order = rng.permutation(rows).astype(np.int32)
+        d_src = torch.from_numpy(src).cuda()
+        d_dst = torch.zeros_like(d_src)
+        hinm.hinm_apply_row_order(d_src, d_dst, torch.from_numpy(order).cuda(), rows, row_bytes)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_dst.cpu().numpy(), src[order])
