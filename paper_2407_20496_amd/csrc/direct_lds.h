@@ -81,13 +81,14 @@ struct RowSegmentCopy {
     odd_k = half ? off[3] : off[2];
   }
 
-  // Issues COPIES wave-wide copies: rows j = 0 .. of this wave (row_base(j) = wave-uniform source address of the
-  // wave's j-th row at the block's first column) land at first_row + j * ROW_BYTES.  The wave's first row must
-  // have an index that is a multiple of four in the stage (it has: waves own 4, 8 or 16 consecutive rows).
-  template <int COPIES, int ROW_BYTES, class RowBase>
-  __device__ __forceinline__ void issue(RowBase row_base, uint8_t* first_row) const {
+  // Issues the wave-wide copies K0 .. K0 + COPIES - 1 of the wave's share of a stage: row_base(j) = wave-uniform
+  // source address of the wave's j-th row at the block's first column; row j lands at first_row + j * ROW_BYTES.
+  // The wave's first row must have an index that is a multiple of four in the stage (it has: waves own 4, 8 or 16
+  // consecutive rows); copy k covers row k (NB = 512) or rows 2 k and 2 k + 1 (NB = 256).
+  template <int K0, int COPIES, int ROW_BYTES, class RowBase>
+  __device__ __forceinline__ void issue_range(RowBase row_base, uint8_t* first_row) const {
 #pragma unroll
-    for (int k = 0; k < COPIES; ++k) {
+    for (int k = K0; k < K0 + COPIES; ++k) {
       if constexpr (NB == 512) {
         copy16_to_lds(row_base(k) + off[k & 3], first_row + k * ROW_BYTES);
       } else {
@@ -96,6 +97,10 @@ struct RowSegmentCopy {
         copy16_to_lds((half ? bo : be) + ((k & 1) ? odd_k : even_k), first_row + 2 * k * ROW_BYTES);
       }
     }
+  }
+  template <int COPIES, int ROW_BYTES, class RowBase>
+  __device__ __forceinline__ void issue(RowBase row_base, uint8_t* first_row) const {
+    issue_range<0, COPIES, ROW_BYTES>(row_base, first_row);
   }
 };
 
