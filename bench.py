@@ -145,6 +145,15 @@ def calibrate(torch, hinm, dev, dtype, quick=True):
             per = (nbytes // wgs) // 8192
             ms = timed(lambda: hinm.hinm_calib_lds_stream(a, nbytes, per * 8192, per, wgs), 3)
             out[f"hbm_to_lds_gbps_{wgs}_workgroups"] = round(wgs * per * 8192 / ms / 1e6, 1)
+        # the tile kernels' request pattern without their stages and barriers: 1 KB segments of rows 16 KB apart,
+        # copied into LDS by 1, 2, 4 or 8 waves of each of 256 workgroups, 16 copies in flight per wave; from a
+        # 4 MB set of rows (L2 hits) and from 16384 rows = 256 MB (beyond L2; the memory-side cache holds part of it)
+        pitch, copies = 16384, 4096
+        for label, rows in (("l2", 256), ("far", 16384)):
+            for waves in (1, 2, 4, 8):
+                per = copies // waves
+                ms = timed(lambda: hinm.hinm_calib_gather_stream(a, nbytes, pitch, rows, waves, 16, per, 256), 3)
+                out[f"gathered_rows_to_lds_gbps_{label}_{waves}_waves"] = round(256 * waves * per * 1024 / ms / 1e6, 1)
         # store-only passes shaped like the C2 output (3072 x 4096 fp16): natural and permuted rows, three piece sizes
         M, N = 3072, 4096
         Ys = [torch.empty((M, N), dtype=torch.int16, device=dev) for _ in range(24)]    # 600 MB rotated

@@ -61,6 +61,17 @@ hinm_status hinm_calib_empty(void* stream);
 hinm_status hinm_calib_lds_stream(const void* region, size_t region_bytes, size_t start_stride_bytes,
                                   int64_t chunks_per_workgroup, int32_t workgroups, void* stream);
 
+/* The request pattern of the tile kernels' gathered input rows, without their stages and barriers: the
+ * first `waves` (1..8) waves of each of `workgroups` workgroups copy copies_per_wave row segments of
+ * 1 KB each straight into LDS, `outstanding` (4, 8 or 16) copies in flight per wave.  The rows are
+ * taken at a fixed stride through [0, rows) of a matrix of `rows` rows of row_pitch_bytes (>= 8192, a
+ * multiple of 16) that starts at `region` (device memory, 16-byte aligned, at least rows x
+ * row_pitch_bytes bytes; only read).  Few rows = a stream of L2 hits, many rows = a stream from
+ * beyond the caches.  Moves workgroups x waves x copies_per_wave KB. */
+hinm_status hinm_calib_gather_stream(const void* region, size_t region_bytes, int64_t row_pitch_bytes, int32_t rows,
+                                     int32_t waves, int32_t outstanding, int32_t copies_per_wave,
+                                     int32_t workgroups, void* stream);
+
 /* One part of the tile kernel that hinm_spmm_prepared would launch for this shape and N, on a real
  * prepared layer (hinm_prepare) and a real X: part 1 = only its copy stream (gathered rows of X and the
  * stored values through L2 into LDS, with the kernel's own barriers and waits; no LDS reads, no MFMAs),

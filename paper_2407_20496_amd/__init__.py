@@ -19,5 +19,5 @@ from .binding import (  # noqa: F401
     hinm_prepare_sizes, hinm_prepare, hinm_spmm_prepared_workspace, hinm_spmm_prepared, hinm_spmm_prepared_plan,
     hinm_status_str, hinm_version,
     calib_symbols, hinm_calib_copy, hinm_calib_fill, hinm_calib_read, hinm_calib_scatter_rows, hinm_calib_smfmac,
-    hinm_calib_empty, hinm_calib_lds_stream, hinm_calib_tile_part,
+    hinm_calib_empty, hinm_calib_lds_stream, hinm_calib_gather_stream, hinm_calib_tile_part,
 )

@@ -47,7 +47,7 @@ def exported_symbols() -> Tuple[str, ...]:
 def calib_symbols() -> Tuple[str, ...]:
     """Entry points include/hinm_calib.h declares (measurement aids)."""
     return ("hinm_calib_copy", "hinm_calib_fill", "hinm_calib_read", "hinm_calib_scatter_rows", "hinm_calib_smfmac",
-            "hinm_calib_empty", "hinm_calib_lds_stream", "hinm_calib_tile_part")
+            "hinm_calib_empty", "hinm_calib_lds_stream", "hinm_calib_gather_stream", "hinm_calib_tile_part")
 
 
 def load_library():
@@ -117,6 +117,8 @@ def load_library():
     lib.hinm_calib_smfmac.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
     lib.hinm_calib_empty.argtypes = [C.c_void_p]
     lib.hinm_calib_lds_stream.argtypes = [C.c_void_p, C.c_size_t, C.c_size_t, C.c_int64, C.c_int32, C.c_void_p]
+    lib.hinm_calib_gather_stream.argtypes = [C.c_void_p, C.c_size_t, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_int32, C.c_void_p]
     lib.hinm_calib_tile_part.argtypes = [sp, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
     for name in calib_symbols():
         getattr(lib, name).restype = C.c_int
@@ -390,6 +392,13 @@ def hinm_calib_lds_stream(region, region_bytes, start_stride_bytes, chunks_per_w
     _check(load_library().hinm_calib_lds_stream(_ptr(region), int(region_bytes), int(start_stride_bytes),
                                                 int(chunks_per_workgroup), int(workgroups), _stream(stream)),
            "hinm_calib_lds_stream")
+
+
+def hinm_calib_gather_stream(region, region_bytes, row_pitch_bytes, rows, waves, outstanding, copies_per_wave, workgroups,
+                             stream=None) -> None:
+    _check(load_library().hinm_calib_gather_stream(_ptr(region), int(region_bytes), int(row_pitch_bytes), int(rows), int(waves),
+                                                   int(outstanding), int(copies_per_wave), int(workgroups), _stream(stream)),
+           "hinm_calib_gather_stream")
 
 
 def hinm_calib_tile_part(M, K, V, Kv, dtype, N, prepared, X, ldx, part, stream=None) -> None:

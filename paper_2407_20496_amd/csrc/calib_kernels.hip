@@ -133,6 +133,30 @@ __global__ __launch_bounds__(kStreamThreads) void calib_lds_stream_kernel(const 
   wait_copies_outstanding<0>();
 }
 
+// Gathered rows: the first `waves` waves of every workgroup each copy `copies` row segments of 1 KB into their own
+// ring of eight LDS slots, OUT copies in flight per wave; the rows are taken at a fixed stride through [0, rows) from
+// a start that depends on workgroup and wave, the segment's column offset on the workgroup (eight different ones).
+// This is the request pattern of the tile kernels' gathered input rows without their stages and barriers.
+template <int OUT>
+__global__ __launch_bounds__(kStreamThreads) void calib_gather_stream_kernel(const uint8_t* __restrict__ region,
+                                                                             int64_t pitch, uint32_t rows, int waves,
+                                                                             int copies) {
+  __shared__ __attribute__((aligned(1024))) uint8_t lds[kStreamLdsBytes];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (wave >= waves) return;
+  uint32_t r = (blockIdx.x * 2654435761u + (uint32_t)wave * 40503u) % rows;
+  const uint32_t step = 7919u % rows;
+  const uint8_t* col = region + (size_t)((blockIdx.x & 7) * 1024) + lane * 16;
+  for (int it = 0; it < copies; ++it) {
+    copy16_to_lds(col + (size_t)r * pitch, lds + (wave * 8 + (it & 7)) * 1024);
+    r += step;
+    if (r >= rows) r -= rows;
+    wait_copies_outstanding<OUT - 1>();
+  }
+  wait_copies_outstanding<0>();
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -210,6 +234,26 @@ hinm_status hinm_calib_lds_stream(const void* region, size_t region_bytes, size_
   calib_lds_stream_kernel<<<(unsigned)workgroups, kStreamThreads, 0, static_cast<hipStream_t>(stream)>>>(
       static_cast<const uint8_t*>(region), (uint32_t)(region_bytes / kStreamChunk),
       (uint32_t)((start_stride_bytes / kStreamChunk) % (region_bytes / kStreamChunk)), chunks_per_workgroup);
+  return hipGetLastError() == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
+}
+
+hinm_status hinm_calib_gather_stream(const void* region, size_t region_bytes, int64_t row_pitch_bytes, int32_t rows,
+                                     int32_t waves, int32_t outstanding, int32_t copies_per_wave, int32_t workgroups,
+                                     void* stream) {
+  if (!region) return HINM_ERR_NULL;
+  if (rows <= 0 || row_pitch_bytes < 8192 || row_pitch_bytes % 16 != 0 || !aligned16(region) ||
+      (size_t)rows * (size_t)row_pitch_bytes > region_bytes || waves < 1 || waves > kStreamThreads / 64 ||
+      copies_per_wave <= 0 || workgroups <= 0)
+    return HINM_ERR_SHAPE;
+  auto s = static_cast<hipStream_t>(stream);
+  const uint8_t* x = static_cast<const uint8_t*>(region);
+  const unsigned g = (unsigned)workgroups;
+  switch (outstanding) {
+    case 4: calib_gather_stream_kernel<4><<<g, kStreamThreads, 0, s>>>(x, row_pitch_bytes, (uint32_t)rows, waves, copies_per_wave); break;
+    case 8: calib_gather_stream_kernel<8><<<g, kStreamThreads, 0, s>>>(x, row_pitch_bytes, (uint32_t)rows, waves, copies_per_wave); break;
+    case 16: calib_gather_stream_kernel<16><<<g, kStreamThreads, 0, s>>>(x, row_pitch_bytes, (uint32_t)rows, waves, copies_per_wave); break;
+    default: return HINM_ERR_UNSUPPORTED;
+  }
   return hipGetLastError() == hipSuccess ? HINM_OK : HINM_ERR_DEVICE;
 }
 

@@ -195,6 +195,11 @@ def test_calibration_entry_points_validate_before_launching():
     assert lib.hinm_calib_smfmac(0, 0, fake, None, None) == 2
     assert lib.hinm_calib_lds_stream(fake, 1000, 0, 1, 1, None) == 2
     assert lib.hinm_calib_lds_stream(fake, 8192, 100, 1, 1, None) == 2
+    assert lib.hinm_calib_gather_stream(None, 1 << 20, 16384, 64, 2, 8, 10, 4, None) == 1
+    assert lib.hinm_calib_gather_stream(fake, 1 << 20, 16384, 65, 2, 8, 10, 4, None) == 2       # rows x pitch beyond the region
+    assert lib.hinm_calib_gather_stream(fake, 1 << 20, 4096, 64, 2, 8, 10, 4, None) == 2        # pitch below 8 KB
+    assert lib.hinm_calib_gather_stream(fake, 1 << 20, 16384, 64, 9, 8, 10, 4, None) == 2       # more waves than a workgroup has
+    assert lib.hinm_calib_gather_stream(fake, 1 << 20, 16384, 64, 2, 5, 10, 4, None) == 5       # copies in flight: 4, 8 or 16
     # a part of the tile kernel: the same argument checks as the product, then only shapes that kernel serves
     sh = binding._shape(256, 512, 64, 256, "bf16")
     assert lib.hinm_calib_tile_part(C.byref(sh), 512, None, fake, 512, 1, None) == 1
