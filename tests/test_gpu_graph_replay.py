@@ -55,7 +55,7 @@ def _check_vs_oracle(case, eager_bits, want_acc):
         gu.check_close(got, want, max_abs=np.inf, what=case.name)
 
 
-def _prepared_case(case, N):
+def _prepared_case(case, N, variant=0):
     import torch
     import paper_2407_20496_amd as hinm
     from tests import gpu_util as gu
@@ -65,14 +65,14 @@ def _prepared_case(case, N):
     ld = N if N == 1 else (N + 7) // 8 * 8
     Xp = np.zeros((case.K, ld), dtype=np.uint16)
     Xp[:, :N] = Xb
-    eager = gu.gpu_spmm_prepared(pr, Xb)
+    eager = gu.gpu_spmm_prepared(pr, Xb, variant=variant)
     _check_vs_oracle(case, eager, _oracle_acc(case, p.host()))
     sets = [(pr.buf if k == 0 else pr.buf.clone(), gu.dev_bits(Xp),
              torch.full((case.M, ld), POISON, dtype=torch.int16, device=gu.DEV)) for k in range(2)]
 
     def launch_all():
         for buf, X, Y in sets:
-            hinm.hinm_spmm_prepared(case.M, case.K, case.V, case.Kv, case.dtype, N, buf, X, ld, Y, ld, 0, None, 0)
+            hinm.hinm_spmm_prepared(case.M, case.K, case.V, case.Kv, case.dtype, N, buf, X, ld, Y, ld, variant << 16, None, 0)
     graph = _capture(torch, launch_all)
     full = np.full((case.M, ld), POISON, dtype=np.uint16)
     full[:, :N] = eager
@@ -90,9 +90,13 @@ def test_graph_replay_decode(idx):
     _prepared_case(c, c.N)
 
 
-def test_graph_replay_tile_kernel_ragged():
+@pytest.mark.parametrize("variant", [3, 16, 14])   # 512-column blocks (copies in chunks), 16 waves, 256-column blocks
+def test_graph_replay_tile_kernel_ragged(variant):
+    import paper_2407_20496_amd as hinm
     c = synth.small_case(384, 2048, 128, 1024, 1100, "bf16", 97)
-    _prepared_case(c, c.N)
+    ld = (c.N + 7) // 8 * 8
+    assert "spmm_tile_prepared_kernel" in hinm.hinm_spmm_prepared_plan(c.M, c.K, c.V, c.Kv, c.dtype, c.N, ld, ld, variant << 16)[0]
+    _prepared_case(c, c.N, variant)
 
 
 def test_graph_replay_canonical_arrays():
