@@ -336,7 +336,7 @@ inline int choose_variant(const PreparedArgs& a) {
   // 64-column waves beyond
   const int64_t blocks = (int64_t)L.T * ((a.N + 255) / 256);
   if (a.N >= 1024 && wide_blocks >= 256 && !narrow_blocks_save_rounds(L, wide_blocks, blocks))
-    return wide_blocks <= 1024 ? 16 : 3;
+    return (wide_blocks <= 1024 || L.RB <= 2) ? 16 : 3;  // tiles of up to 64 rows: sixteen waves measured 1-5 % ahead at any size
   // ... and wherever they save rounds of workgroups: a round is one serial pass over the kept columns however
   // few workgroups it holds, and a pass of a 512-column block costs about 1.35 passes of a 256-column block
   // (11008 x 4096 at N = 768: 258 narrow blocks, two rounds, 72 us; 172 wide blocks, one round, 47 us).  For
